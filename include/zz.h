@@ -1,0 +1,163 @@
+/*
+ * zz.h - C ABI of the ZigzagAttention inference hot path for AMD MI355X (gfx950).
+ *
+ * What the library computes (arXiv 2508.12407):
+ *   - Section 2.2: every transformer layer is either all-retrieval or all-streaming
+ *     (p of L layers streaming), so a layer needs exactly one attention launch.
+ *   - Sections 1 and 2.1: a retrieval head runs full causal attention over every
+ *     cached token; a streaming head keeps only the attention-sink tokens and a
+ *     recent window and waives the rest of its KV cache.
+ *   - Section 3.3: sink size S and window length W parameterise streaming attention.
+ *   - Section 2.1 (last paragraph): the DuoAttention layout mixes both kinds of
+ *     head inside one layer and pays two attention launches per layer; it is
+ *     available here as ZZ_MIXED, the comparison baseline.
+ *
+ * Readings where the paper is silent: the window is the W newest positions
+ * including the query's own (a streaming head sees at most S+W tokens); the kind
+ * is a property of a KV head (all Hq/Hkv query heads of its group follow it);
+ * keys arrive already position-encoded; softmax scale defaults to 1/sqrt(head_dim).
+ *
+ * Conventions for every entry point
+ *   - All tensors are bf16 (16-bit brain float), contiguous, 16-byte aligned DEVICE
+ *     memory owned by the caller.  The KV arena and the workspace are caller-owned
+ *     DEVICE memory too.  `zz_config` and the two mask arrays are HOST memory and are
+ *     copied by zz_create.  `zz_ctx` is host memory owned by the library.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue kernels: the library never allocates device memory, never
+ *     synchronises and never copies the arena.
+ *   - Return value: 0 (ZZ_OK) or a negative ZZ_E* code.  All argument checks run on
+ *     the host before anything is launched; a call that fails has launched nothing
+ *     and changed no length.  n_new == 0 is a successful no-op.
+ *   - All B sequences of a batch share one length per layer.
+ *   - A context must not be used from two host threads at once.
+ */
+#ifndef ZZ_H
+#define ZZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZZ_TILE_SLOTS 32   /* cache slots per KV tile                                   */
+#define ZZ_MAX_KV_HEADS 64 /* upper bound on n_kv_heads                                  */
+#define ZZ_MAX_SPLITS 128  /* upper bound on split-K partials per (batch, query head)    */
+
+enum {
+  ZZ_OK = 0,
+  ZZ_EINVAL = -1,       /* null pointer, non-positive size, bad enum                      */
+  ZZ_ERANGE = -2,       /* layer / head / n_new out of range                              */
+  ZZ_ENOSPC = -3,       /* append past max_ctx; arena or workspace too small              */
+  ZZ_EALIGN = -4,       /* a device pointer is not 16-byte (arena: 256-byte) aligned      */
+  ZZ_ESTATE = -5,       /* decode on an empty layer; mask missing for the chosen layout   */
+  ZZ_EUNSUPPORTED = -6, /* head_dim, group size or head count outside what is built       */
+  ZZ_EHIP = -7          /* a kernel launch was rejected by the HIP runtime                */
+};
+
+enum { ZZ_ZIGZAG = 0, ZZ_MIXED = 1 };
+
+typedef struct zz_ctx zz_ctx;
+
+typedef struct zz_config {
+  int32_t n_layers;   /* L >= 1                                                           */
+  int32_t n_q_heads;  /* Hq, multiple of n_kv_heads, Hq / Hkv <= 16                       */
+  int32_t n_kv_heads; /* Hkv <= ZZ_MAX_KV_HEADS                                           */
+  int32_t head_dim;   /* D: 64 or 128                                                     */
+  int32_t batch;      /* B >= 1                                                           */
+  int32_t max_ctx;    /* capacity of a retrieval cache, tokens                            */
+  int32_t sink;       /* S >= 0  (Section 3.3)                                            */
+  int32_t window;     /* W >= 1  (Section 3.3), includes the query's own position         */
+  int32_t max_chunk;  /* largest n_new accepted by zz_attn_prefill (0: prefill unused)    */
+  int32_t layout;     /* ZZ_ZIGZAG or ZZ_MIXED                                            */
+  float softmax_scale;                /* 0 => 1/sqrt(head_dim)                            */
+  const uint8_t *layer_is_streaming;  /* HOST [n_layers]; required for ZZ_ZIGZAG          */
+  const uint8_t *kvhead_is_streaming; /* HOST [n_layers*n_kv_heads]; required for ZZ_MIXED */
+} zz_config;
+
+/* Bytes of device memory the caller must provide.  0 if the config is invalid. */
+size_t zz_arena_bytes(const zz_config *cfg);
+size_t zz_workspace_bytes(const zz_config *cfg);
+
+/* Validate `cfg`, lay the per-layer caches out inside `kv_arena` (256-byte aligned)
+ * and create a context with every layer empty.  The arena is not touched. */
+int zz_create(const zz_config *cfg, void *kv_arena, size_t arena_bytes, void *workspace,
+              size_t workspace_bytes, zz_ctx **out);
+int zz_destroy(zz_ctx *ctx);
+int zz_reset(zz_ctx *ctx); /* all layer lengths := 0 */
+
+/* Append n_new tokens to layer `layer` (Sections 1 and 3.3: a retrieval head keeps
+ * every token, a streaming head keeps the S sink tokens plus the W newest ones).
+ * k_new, v_new: DEVICE [B, n_new, Hkv, D].  A token at position pos goes to slot
+ * zz_slot_of(pos); a streaming ring slot is overwritten by the token W positions
+ * later, which is the eviction.  The result equals n_new single-token appends.
+ * ZZ_ENOSPC if the layer's length would exceed max_ctx (lengths of all layers, also
+ * all-streaming ones, are bounded by max_ctx). */
+int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new, void *stream);
+
+/* Attention for n_new new query positions [len, len + n_new) of layer `layer`, where
+ * len = zz_layer_len(layer), over the cached tokens followed by (k_new, v_new)
+ * (Section 1: prefilling phase; masks as above, each query at its own position).
+ * q, out: DEVICE [B, n_new, Hq, D]; k_new, v_new: DEVICE [B, n_new, Hkv, D].
+ * Does not change the cache: call zz_kv_append with the same k_new, v_new afterwards.
+ * 1 <= n_new <= max_chunk.  Uses the workspace; calls on one context must be stream-ordered. */
+int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new,
+                    int n_new, void *out, void *stream);
+
+/* Attention for the newest cached position of layer `layer` (Section 1: decoding
+ * phase): call after zz_kv_append(..., 1).  q, out: DEVICE [B, Hq, D].
+ * ZZ_ESTATE if the layer is empty.  Uses the workspace. */
+int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream);
+
+/* Tokens appended to the layer so far, or a negative error code. */
+int64_t zz_layer_len(const zz_ctx *ctx, int layer);
+/* Overwrite a layer's length (restoring a snapshot of the arena). 0 <= len <= max_ctx. */
+int zz_set_layer_len(zz_ctx *ctx, int layer, int64_t len);
+
+/* Attention launches zz_attn_decode issues for this layer: 1 for a zigzag layer
+ * (Section 2.2), 2 for a mixed layer holding both kinds of head (Section 2.1). */
+int zz_layer_launches(const zz_ctx *ctx, int layer);
+
+/* Pure host arithmetic: the cache slot a token at position `pos` of (layer, kv_head)
+ * is written to.  Retrieval: pos.  Streaming: pos if pos < S, else S + (pos - S) mod W.
+ * Negative error code on bad arguments (ZZ_ERANGE if pos >= max_ctx on a retrieval head). */
+int64_t zz_slot_of(const zz_config *cfg, int layer, int kv_head, int64_t pos);
+
+/* Pure host arithmetic: byte offset inside the arena of element d of slot `slot`
+ * of (layer, batch b, kv_head); which = 0 for K, 1 for V.  Negative on bad arguments.
+ *
+ * Arena layout.  Layers in order; inside a layer first the retrieval heads' region,
+ * then the streaming heads' region (one of the two is empty in a zigzag layer).  A
+ * region is [B][heads of that kind, ascending][n_tiles] KV tiles with
+ * n_tiles = ceil(capacity / 32), capacity = max_ctx or S + W.  A KV tile holds 32
+ * consecutive slots: 64*D bytes of K followed by 64*D bytes of V, each stored in the
+ * register image of the 16x16x32 bf16 MFMA operand it feeds, so a wavefront streams
+ * a tile with sixteen (D = 128) fully coalesced 1 KiB loads and no shuffling.
+ * For slot-in-tile t (0..31) and element d (0..D-1):
+ *   K: element index ((( (t/16)*(D/8) + d/8 )*16 + t%16 )*8 + d%8)
+ *   V: element index ((( (d/16)*4 + (t%16)/4 )*16 + d%16 )*8 + 4*(t/16) + t%4) + 32*D
+ * (element index * 2 = byte offset inside the tile). */
+int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv_head, int64_t slot, int d);
+
+/* Tuning knobs, for measurement.  key: */
+enum {
+  ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 2)  */
+  ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
+  ZZ_TUNE_NUM_CU = 3             /* override the detected compute-unit count               */
+};
+int zz_tune(zz_ctx *ctx, int key, int value);
+
+/* Split count and tiles per split the next zz_attn_decode would use for group
+ * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty. */
+int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
+
+const char *zz_strerror(int code);
+/* What the HIP runtime reported for the calling thread's most recent ZZ_EHIP
+ * (which kernel, hipGetErrorString text); "" if there was none. */
+const char *zz_last_error_detail(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZZ_H */

@@ -1,0 +1,454 @@
+// Host runtime behind the C ABI in include/zz.h: config validation, arena layout,
+// per-layer length tracking, slot arithmetic and launch planning.  Everything here
+// is integer host code and runs without a GPU; only the zz_launch_* calls touch HIP.
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "zz_internal.h"
+
+namespace {
+
+struct Group {
+  int n_heads = 0;
+  uint8_t heads[ZZ_MAX_KV_HEADS] = {0};
+  int64_t capacity = 0;  // slots per (batch, head)
+  int n_tiles = 0;       // ceil(capacity / 32)
+  size_t base = 0;       // byte offset of the region in the arena
+  bool streaming = false;
+};
+
+struct Layer {
+  Group grp[2];  // 0: retrieval heads, 1: streaming heads
+  uint8_t head_group[ZZ_MAX_KV_HEADS] = {0};
+  uint8_t head_index[ZZ_MAX_KV_HEADS] = {0};
+  int64_t len = 0;
+};
+
+struct Layout {
+  std::vector<Layer> layers;
+  size_t arena_bytes = 0;
+  size_t ws_part_o = 0, ws_part_ml = 0, ws_stage = 0, ws_bytes = 0;
+  int stage_tiles = 0;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t kv_tile_bytes(int D) { return (size_t)2 * ZZ_TILE_SLOTS * D * 2; }
+
+int validate(const zz_config *c) {
+  if (!c) return ZZ_EINVAL;
+  if (c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->batch < 1 || c->max_ctx < 1) return ZZ_EINVAL;
+  if (c->sink < 0 || c->window < 1 || c->max_chunk < 0) return ZZ_EINVAL;
+  if (c->layout != ZZ_ZIGZAG && c->layout != ZZ_MIXED) return ZZ_EINVAL;
+  if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale)) return ZZ_EINVAL;
+  if (c->head_dim != 64 && c->head_dim != 128) return ZZ_EUNSUPPORTED;
+  if (c->n_kv_heads > ZZ_MAX_KV_HEADS) return ZZ_EUNSUPPORTED;
+  if (c->n_q_heads % c->n_kv_heads != 0) return ZZ_EINVAL;
+  if (c->n_q_heads / c->n_kv_heads > 16) return ZZ_EUNSUPPORTED;
+  if ((int64_t)c->sink + c->window > (int64_t)1 << 30 || c->max_ctx > (1 << 30)) return ZZ_EUNSUPPORTED;
+  if (c->layout == ZZ_ZIGZAG && !c->layer_is_streaming) return ZZ_ESTATE;
+  if (c->layout == ZZ_MIXED && !c->kvhead_is_streaming) return ZZ_ESTATE;
+  return ZZ_OK;
+}
+
+bool head_streams(const zz_config *c, int layer, int g) {
+  if (c->layout == ZZ_ZIGZAG) return c->layer_is_streaming[layer] != 0;
+  return c->kvhead_is_streaming[(size_t)layer * c->n_kv_heads + g] != 0;
+}
+
+// Lays out every layer's regions; assumes validate() passed.
+void build_layout(const zz_config *c, Layout *lo) {
+  const size_t tile = kv_tile_bytes(c->head_dim);
+  lo->layers.assign(c->n_layers, Layer());
+  size_t off = 0;
+  for (int l = 0; l < c->n_layers; ++l) {
+    Layer &L = lo->layers[l];
+    L.grp[0].streaming = false;
+    L.grp[1].streaming = true;
+    for (int g = 0; g < c->n_kv_heads; ++g) {
+      Group &G = L.grp[head_streams(c, l, g) ? 1 : 0];
+      L.head_group[g] = head_streams(c, l, g) ? 1 : 0;
+      L.head_index[g] = (uint8_t)G.n_heads;
+      G.heads[G.n_heads++] = (uint8_t)g;
+    }
+    for (int k = 0; k < 2; ++k) {
+      Group &G = L.grp[k];
+      G.capacity = k ? (int64_t)c->sink + c->window : (int64_t)c->max_ctx;
+      G.n_tiles = (int)ceil_div(G.capacity, ZZ_TILE_SLOTS);
+      G.base = off;
+      off += (size_t)c->batch * G.n_heads * G.n_tiles * tile;
+      off = align_up(off, 256);
+    }
+  }
+  lo->arena_bytes = off;
+  size_t w = 0;
+  lo->ws_part_o = w;
+  w += align_up((size_t)c->batch * c->n_q_heads * ZZ_MAX_SPLITS * c->head_dim * sizeof(float), 256);
+  lo->ws_part_ml = w;
+  w += align_up((size_t)c->batch * c->n_q_heads * ZZ_MAX_SPLITS * 2 * sizeof(float), 256);
+  lo->ws_stage = w;
+  lo->stage_tiles = (int)ceil_div(c->max_chunk, ZZ_TILE_SLOTS);
+  w += align_up((size_t)c->batch * c->n_kv_heads * lo->stage_tiles * tile, 256);
+  lo->ws_bytes = w;
+}
+
+inline int64_t slot_rule(bool streaming, int64_t pos, int64_t S, int64_t W) {
+  if (!streaming || pos < S) return pos;
+  return S + (pos - S) % W;
+}
+
+}  // namespace
+
+struct zz_ctx {
+  zz_config cfg;
+  std::vector<uint8_t> layer_mask, head_mask;
+  Layout lo;
+  char *arena = nullptr;
+  char *ws = nullptr;
+  float scale = 0.f;
+  int num_cu = 0;          // 0: not queried yet
+  int tune_wg_per_cu = 2;
+  int tune_splits = 0;
+};
+
+namespace {
+
+zz_group_dev dev_group(const zz_ctx *ctx, const Group &G) {
+  zz_group_dev d;
+  d.base = ctx->arena + G.base;
+  d.n_heads = G.n_heads;
+  d.n_tiles = G.n_tiles;
+  d.streaming = G.streaming ? 1 : 0;
+  d.pad_ = 0;
+  return d;
+}
+
+thread_local char g_detail[256] = "";
+
+// Records what the HIP runtime said about a rejected launch and maps it to ZZ_EHIP.
+int hip_failed(const char *what, hipError_t e) {
+  std::snprintf(g_detail, sizeof(g_detail), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+  return ZZ_EHIP;
+}
+
+inline bool misaligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+int check_layer(const zz_ctx *ctx, int layer) {
+  if (!ctx) return ZZ_EINVAL;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return ZZ_ERANGE;
+  return ZZ_OK;
+}
+
+int64_t occupied(const zz_ctx *ctx, const Group &G, int64_t len) {
+  return G.streaming ? (len < G.capacity ? len : G.capacity) : len;
+}
+
+int num_cu(zz_ctx *ctx) {
+  if (ctx->num_cu <= 0) {
+    int n = zz_query_num_cu();
+    ctx->num_cu = n > 0 ? n : 256;
+  }
+  return ctx->num_cu;
+}
+
+// Split-K plan for one group: enough workgroups to fill the chip, at least one
+// tile per wave of a workgroup, never more partials than the workspace holds.
+void plan_decode(const zz_ctx *ctx, int cu, const Group &G, int64_t len, int *n_splits, int *tiles_per_split) {
+  const int64_t n_valid = occupied(ctx, G, len);
+  const int64_t n_tiles = ceil_div(n_valid, ZZ_TILE_SLOTS);
+  if (G.n_heads == 0 || n_tiles == 0) {
+    *n_splits = 0;
+    *tiles_per_split = 0;
+    return;
+  }
+  const int64_t units = (int64_t)ctx->cfg.batch * G.n_heads;
+  int64_t splits = ctx->tune_splits > 0 ? ctx->tune_splits : ceil_div((int64_t)cu * ctx->tune_wg_per_cu, units);
+  if (splits < 1) splits = 1;
+  int64_t tps = ceil_div(n_tiles, splits);
+  if (tps < ZZ_WAVES_PER_WG && ctx->tune_splits <= 0) tps = ZZ_WAVES_PER_WG;
+  if (tps > n_tiles) tps = n_tiles;
+  splits = ceil_div(n_tiles, tps);
+  if (splits > ZZ_MAX_SPLITS) {
+    tps = ceil_div(n_tiles, ZZ_MAX_SPLITS);
+    splits = ceil_div(n_tiles, tps);
+  }
+  *n_splits = (int)splits;
+  *tiles_per_split = (int)tps;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t zz_arena_bytes(const zz_config *cfg) {
+  if (validate(cfg) != ZZ_OK) return 0;
+  Layout lo;
+  build_layout(cfg, &lo);
+  return lo.arena_bytes;
+}
+
+size_t zz_workspace_bytes(const zz_config *cfg) {
+  if (validate(cfg) != ZZ_OK) return 0;
+  Layout lo;
+  build_layout(cfg, &lo);
+  return lo.ws_bytes;
+}
+
+int zz_create(const zz_config *cfg, void *kv_arena, size_t arena_bytes, void *workspace, size_t workspace_bytes,
+              zz_ctx **out) {
+  if (!out) return ZZ_EINVAL;
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc != ZZ_OK) return rc;
+  if (!kv_arena || !workspace) return ZZ_EINVAL;
+  if (misaligned(kv_arena, 256) || misaligned(workspace, 256)) return ZZ_EALIGN;
+  zz_ctx *ctx = new (std::nothrow) zz_ctx();
+  if (!ctx) return ZZ_ENOSPC;
+  ctx->cfg = *cfg;
+  if (cfg->layout == ZZ_ZIGZAG) {
+    ctx->layer_mask.assign(cfg->layer_is_streaming, cfg->layer_is_streaming + cfg->n_layers);
+    ctx->cfg.layer_is_streaming = ctx->layer_mask.data();
+    ctx->cfg.kvhead_is_streaming = nullptr;
+  } else {
+    ctx->head_mask.assign(cfg->kvhead_is_streaming,
+                          cfg->kvhead_is_streaming + (size_t)cfg->n_layers * cfg->n_kv_heads);
+    ctx->cfg.kvhead_is_streaming = ctx->head_mask.data();
+    ctx->cfg.layer_is_streaming = nullptr;
+  }
+  build_layout(&ctx->cfg, &ctx->lo);
+  if (arena_bytes < ctx->lo.arena_bytes || workspace_bytes < ctx->lo.ws_bytes) {
+    delete ctx;
+    return ZZ_ENOSPC;
+  }
+  ctx->arena = (char *)kv_arena;
+  ctx->ws = (char *)workspace;
+  ctx->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  *out = ctx;
+  return ZZ_OK;
+}
+
+int zz_destroy(zz_ctx *ctx) {
+  if (!ctx) return ZZ_EINVAL;
+  delete ctx;
+  return ZZ_OK;
+}
+
+int zz_reset(zz_ctx *ctx) {
+  if (!ctx) return ZZ_EINVAL;
+  for (auto &L : ctx->lo.layers) L.len = 0;
+  return ZZ_OK;
+}
+
+int64_t zz_layer_len(const zz_ctx *ctx, int layer) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  return ctx->lo.layers[layer].len;
+}
+
+int zz_set_layer_len(zz_ctx *ctx, int layer, int64_t len) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (len < 0 || len > ctx->cfg.max_ctx) return ZZ_ERANGE;
+  ctx->lo.layers[layer].len = len;
+  return ZZ_OK;
+}
+
+int zz_layer_launches(const zz_ctx *ctx, int layer) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  const Layer &L = ctx->lo.layers[layer];
+  return (L.grp[0].n_heads > 0) + (L.grp[1].n_heads > 0);
+}
+
+int64_t zz_slot_of(const zz_config *cfg, int layer, int kv_head, int64_t pos) {
+  int rc = validate(cfg);
+  if (rc != ZZ_OK) return rc;
+  if (layer < 0 || layer >= cfg->n_layers || kv_head < 0 || kv_head >= cfg->n_kv_heads || pos < 0) return ZZ_ERANGE;
+  const bool st = head_streams(cfg, layer, kv_head);
+  if (!st && pos >= cfg->max_ctx) return ZZ_ERANGE;
+  return slot_rule(st, pos, cfg->sink, cfg->window);
+}
+
+int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv_head, int64_t slot, int d) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  const zz_config &c = ctx->cfg;
+  if (which < 0 || which > 1) return ZZ_EINVAL;
+  if (b < 0 || b >= c.batch || kv_head < 0 || kv_head >= c.n_kv_heads || d < 0 || d >= c.head_dim) return ZZ_ERANGE;
+  const Layer &L = ctx->lo.layers[layer];
+  const Group &G = L.grp[L.head_group[kv_head]];
+  if (slot < 0 || slot >= G.capacity) return ZZ_ERANGE;
+  const int64_t D = c.head_dim;
+  const int64_t tile = slot / ZZ_TILE_SLOTS, t = slot % ZZ_TILE_SLOTS;
+  int64_t elem;
+  if (which == 0)
+    elem = (((t / 16) * (D / 8) + d / 8) * 16 + t % 16) * 8 + d % 8;
+  else
+    elem = ((((int64_t)(d / 16) * 4 + (t % 16) / 4) * 16 + d % 16) * 8 + 4 * (t / 16) + t % 4) + 32 * D;
+  const int64_t tile_index = ((int64_t)b * G.n_heads + L.head_index[kv_head]) * G.n_tiles + tile;
+  return (int64_t)G.base + tile_index * (int64_t)kv_tile_bytes(c.head_dim) + elem * 2;
+}
+
+int zz_tune(zz_ctx *ctx, int key, int value) {
+  if (!ctx) return ZZ_EINVAL;
+  switch (key) {
+    case ZZ_TUNE_DECODE_WG_PER_CU:
+      if (value < 1 || value > 64) return ZZ_ERANGE;
+      ctx->tune_wg_per_cu = value;
+      return ZZ_OK;
+    case ZZ_TUNE_DECODE_SPLITS:
+      if (value < 0 || value > ZZ_MAX_SPLITS) return ZZ_ERANGE;
+      ctx->tune_splits = value;
+      return ZZ_OK;
+    case ZZ_TUNE_NUM_CU:
+      if (value < 1 || value > 4096) return ZZ_ERANGE;
+      ctx->num_cu = value;
+      return ZZ_OK;
+    default:
+      return ZZ_EINVAL;
+  }
+}
+
+int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (group < 0 || group > 1 || !n_splits || !tiles_per_split) return ZZ_EINVAL;
+  const Layer &L = ctx->lo.layers[layer];
+  plan_decode(ctx, num_cu(const_cast<zz_ctx *>(ctx)), L.grp[group], L.len, n_splits, tiles_per_split);
+  return ZZ_OK;
+}
+
+int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new, void *stream) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (n_new < 0) return ZZ_ERANGE;
+  if (n_new == 0) return ZZ_OK;
+  if (!k_new || !v_new) return ZZ_EINVAL;
+  if (misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
+  Layer &L = ctx->lo.layers[layer];
+  const zz_config &c = ctx->cfg;
+  if (L.len + n_new > c.max_ctx) return ZZ_ENOSPC;  // the length counter itself is bounded by max_ctx
+  zz_append_params p;
+  std::memset(&p, 0, sizeof(p));
+  p.k_new = k_new;
+  p.v_new = v_new;
+  p.grp[0] = dev_group(ctx, L.grp[0]);
+  p.grp[1] = dev_group(ctx, L.grp[1]);
+  std::memcpy(p.head_group, L.head_group, sizeof(p.head_group));
+  std::memcpy(p.head_index, L.head_index, sizeof(p.head_index));
+  p.len = L.len;
+  p.n_new = n_new;
+  p.batch = c.batch;
+  p.n_kv_heads = c.n_kv_heads;
+  p.head_dim = c.head_dim;
+  p.sink = c.sink;
+  p.window = c.window;
+  if (hipError_t e = zz_launch_append(p, (hipStream_t)stream)) return hip_failed("append kernel", e);
+  L.len += n_new;
+  return ZZ_OK;
+}
+
+int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (!q || !out) return ZZ_EINVAL;
+  if (misaligned(q, 16) || misaligned(out, 16)) return ZZ_EALIGN;
+  Layer &L = ctx->lo.layers[layer];
+  if (L.len <= 0) return ZZ_ESTATE;
+  const zz_config &c = ctx->cfg;
+  const int cu = num_cu(ctx);
+  for (int k = 0; k < 2; ++k) {
+    const Group &G = L.grp[k];
+    if (G.n_heads == 0) continue;
+    zz_decode_params p;
+    std::memset(&p, 0, sizeof(p));
+    p.grp = dev_group(ctx, G);
+    std::memcpy(p.heads, G.heads, sizeof(p.heads));
+    p.q = q;
+    p.out = out;
+    p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
+    p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
+    p.n_valid = (int)occupied(ctx, G, L.len);
+    p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
+    plan_decode(ctx, cu, G, L.len, &p.n_splits, &p.tiles_per_split);
+    p.batch = c.batch;
+    p.n_q_heads = c.n_q_heads;
+    p.n_kv_heads = c.n_kv_heads;
+    p.head_dim = c.head_dim;
+    p.group_size = c.n_q_heads / c.n_kv_heads;
+    p.scale_log2e = ctx->scale * 1.4426950408889634f;
+    if (hipError_t e = zz_launch_decode(p, (hipStream_t)stream)) return hip_failed("decode kernel", e);
+  }
+  return ZZ_OK;
+}
+
+int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, int n_new,
+                    void *out, void *stream) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (n_new < 0) return ZZ_ERANGE;
+  if (n_new == 0) return ZZ_OK;
+  if (!q || !k_new || !v_new || !out) return ZZ_EINVAL;
+  if (misaligned(q, 16) || misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(out, 16)) return ZZ_EALIGN;
+  const zz_config &c = ctx->cfg;
+  if (n_new > c.max_chunk) return ZZ_ERANGE;
+  Layer &L = ctx->lo.layers[layer];
+  if (L.len + n_new > c.max_ctx) return ZZ_ENOSPC;
+  zz_stage_params sp;
+  std::memset(&sp, 0, sizeof(sp));
+  sp.k_new = k_new;
+  sp.v_new = v_new;
+  sp.stage = ctx->ws + ctx->lo.ws_stage;
+  sp.stage_tiles = ctx->lo.stage_tiles;
+  sp.n_new = n_new;
+  sp.batch = c.batch;
+  sp.n_kv_heads = c.n_kv_heads;
+  sp.head_dim = c.head_dim;
+  if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
+  for (int k = 0; k < 2; ++k) {
+    const Group &G = L.grp[k];
+    if (G.n_heads == 0) continue;
+    zz_prefill_params p;
+    std::memset(&p, 0, sizeof(p));
+    p.grp = dev_group(ctx, G);
+    std::memcpy(p.heads, G.heads, sizeof(p.heads));
+    p.q = q;
+    p.out = out;
+    p.stage = sp.stage;
+    p.stage_tiles = sp.stage_tiles;
+    p.n_past = (int)L.len;
+    p.n_new = n_new;
+    p.batch = c.batch;
+    p.n_q_heads = c.n_q_heads;
+    p.n_kv_heads = c.n_kv_heads;
+    p.head_dim = c.head_dim;
+    p.group_size = c.n_q_heads / c.n_kv_heads;
+    p.sink = c.sink;
+    p.window = c.window;
+    p.scale_log2e = ctx->scale * 1.4426950408889634f;
+    if (hipError_t e = zz_launch_prefill(p, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+  }
+  return ZZ_OK;
+}
+
+const char *zz_last_error_detail(void) { return g_detail; }
+
+const char *zz_strerror(int code) {
+  switch (code) {
+    case ZZ_OK: return "ok";
+    case ZZ_EINVAL: return "invalid argument (null pointer, non-positive size or unknown enum)";
+    case ZZ_ERANGE: return "layer, head, position or token count out of range";
+    case ZZ_ENOSPC: return "no space: append past max_ctx, or arena/workspace too small";
+    case ZZ_EALIGN: return "pointer not aligned (tensors 16 bytes, arena and workspace 256 bytes)";
+    case ZZ_ESTATE: return "wrong state: empty layer, or the mask for the chosen layout is missing";
+    case ZZ_EUNSUPPORTED: return "unsupported shape (head_dim must be 64 or 128, Hq/Hkv <= 16, Hkv <= 64)";
+    case ZZ_EHIP: return "the HIP runtime rejected a kernel launch";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

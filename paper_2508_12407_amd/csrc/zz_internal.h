@@ -1,0 +1,75 @@
+// Internal interface between the host runtime (zz_api.cpp) and the gfx950 kernels
+// (zz_kernels.hip).  Plain structs passed by value as kernel arguments: the library
+// owns no device memory, so per-launch tables (head lists) travel in the argument
+// buffer instead.
+#ifndef ZZ_INTERNAL_H
+#define ZZ_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "zz.h"
+
+#define ZZ_WAVES_PER_WG 4
+
+// One head group of a layer: the heads of one kind (retrieval or streaming).
+struct zz_group_dev {
+  char *base;          // arena address of the group's region: [B][n_heads][n_tiles] KV tiles
+  int32_t n_heads;     // KV heads in the group
+  int32_t n_tiles;     // tiles per (batch, head) = ceil(capacity / 32)
+  int32_t streaming;   // 1: sink + ring slots; 0: slot == position
+  int32_t pad_;
+};
+
+struct zz_append_params {
+  const void *k_new, *v_new;      // [B, n_new, Hkv, D] bf16
+  zz_group_dev grp[2];
+  uint8_t head_group[ZZ_MAX_KV_HEADS];  // kv head -> group (0/1)
+  uint8_t head_index[ZZ_MAX_KV_HEADS];  // kv head -> index inside its group
+  int64_t len;                    // tokens already in the layer
+  int32_t n_new, batch, n_kv_heads, head_dim;
+  int32_t sink, window;
+};
+
+struct zz_decode_params {
+  zz_group_dev grp;
+  uint8_t heads[ZZ_MAX_KV_HEADS]; // kv head ids of the group, ascending
+  const void *q;                  // [B, Hq, D] bf16
+  void *out;                      // [B, Hq, D] bf16
+  float *part_o;                  // [B, Hq, ZZ_MAX_SPLITS, D]
+  float *part_ml;                 // [B, Hq, ZZ_MAX_SPLITS, 2]  (max in log2 units, sum)
+  int32_t n_valid;                // occupied slots (prefix of the cache)
+  int32_t n_tiles_valid;          // ceil(n_valid / 32)
+  int32_t tiles_per_split, n_splits;
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, group_size;
+  float scale_log2e;              // softmax scale * log2(e)
+};
+
+// Where the keys of a prefill call come from: cached tiles, then the staged chunk.
+struct zz_prefill_params {
+  zz_group_dev grp;
+  uint8_t heads[ZZ_MAX_KV_HEADS];
+  const void *q;                  // [B, n_new, Hq, D]
+  void *out;                      // [B, n_new, Hq, D]
+  const char *stage;              // staged chunk: [B][Hkv][stage_tiles] KV tiles, token idx -> slot idx
+  int32_t stage_tiles;            // tiles per (batch, kv head) in the staging area (stride)
+  int32_t n_past;                 // tokens already cached (query positions start here)
+  int32_t n_new;
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, group_size;
+  int32_t sink, window;
+  float scale_log2e;
+};
+
+struct zz_stage_params {
+  const void *k_new, *v_new;      // [B, n_new, Hkv, D]
+  char *stage;
+  int32_t stage_tiles, n_new, batch, n_kv_heads, head_dim;
+};
+
+hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s);
+hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
+hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
+hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s);
+int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable
+
+#endif

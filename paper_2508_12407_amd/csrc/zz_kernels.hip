@@ -1,0 +1,536 @@
+// gfx950 (CDNA4, MI355X) kernels of the ZigzagAttention hot path.
+//
+// Data layout.  The KV cache is stored in "KV tiles" of 32 slots: 64*D bytes of K
+// then 64*D bytes of V, each laid out as the register image of the operand it
+// feeds to v_mfma_f32_16x16x32_bf16, so lane L's i-th 16-byte load of a tile is at
+// byte i*1024 + L*16 and a wavefront streams a tile as 1 KiB contiguous loads with
+// no LDS staging and no shuffles.
+//
+// MFMA operand convention used throughout (16x16x32, A: MxK, B: KxN, C: MxN):
+//   lane L supplies A[m = L%16][k = 8*(L/16) .. +7] and B[k = 8*(L/16) .. +7][n = L%16],
+//   and receives C[m = 4*(L/16) + r][n = L%16], r = 0..3.
+// Scores:  S^T[token][column] = K[token][:] . Q[column][:]   (A = K tile, B = Q)
+// Output:  O^T[d][column]    = sum_token V[token][d] P[token][column]  (A = V tile, B = P)
+// A "column" is one of up to 16 query rows sharing the KV head: the G query heads
+// of the group in decode, 16 query positions of one head in prefill.  The lane that
+// holds score rows 4*kg+r of token blocks 0 and 1 is exactly the lane that must
+// supply P for k = 8*kg .. +7, once the V tile orders its tokens that way, so the
+// probabilities never move between lanes.
+#include <hip/hip_runtime.h>
+
+#include "zz_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define ZZ_NEG_INF (-__builtin_inff())
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// --------------------------------------------------------------------------
+// Append / evict: scatter new K, V rows into their tiles.
+// One thread per (batch, new token, kv head, 8-element chunk of the head vector).
+// --------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
+  constexpr int CH = D / 8;
+  const int64_t total = (int64_t)p.batch * p.n_new * p.n_kv_heads * CH;
+  int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (tid >= total) return;
+  const int c = (int)(tid % CH);
+  tid /= CH;
+  const int g = (int)(tid % p.n_kv_heads);
+  tid /= p.n_kv_heads;
+  const int idx = (int)(tid % p.n_new);
+  const int b = (int)(tid / p.n_new);
+
+  const zz_group_dev &G = p.grp[p.head_group[g]];
+  const int64_t pos = p.len + idx;
+  int64_t slot = pos;
+  if (G.streaming && pos >= p.sink) {
+    // a ring token that a later token of this same call overwrites is never written,
+    // so the result does not depend on the order threads run in
+    if (pos + p.window <= p.len + p.n_new - 1) return;
+    slot = p.sink + (pos - p.sink) % p.window;
+  }
+  const int64_t src = ((((int64_t)b * p.n_new + idx) * p.n_kv_heads + g) * D) / 8 + c;
+  const uint4 kv = ((const uint4 *)p.k_new)[src];
+  const uint4 vv = ((const uint4 *)p.v_new)[src];
+
+  const int64_t tile = slot / ZZ_TILE_SLOTS;
+  const int t = (int)(slot % ZZ_TILE_SLOTS);
+  char *tb = G.base + (((int64_t)b * G.n_heads + p.head_index[g]) * G.n_tiles + tile) * (int64_t)(128 * D);
+  // K: 16-byte chunk c of the row -> [t/16][c][t%16]
+  ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = kv;
+  // V: element d -> [d/16][(t%16)/4][d%16][4*(t/16) + t%4], after the 64*D bytes of K
+  unsigned short *vt = (unsigned short *)tb + 32 * D;
+  const unsigned int w[4] = {vv.x, vv.y, vv.z, vv.w};
+  const int e = 4 * (t >> 4) + (t & 3);
+  const int kgv = (t & 15) >> 2;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int d = 8 * c + i;
+    const unsigned short val = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xffffu));
+    vt[((((d >> 4) * 4 + kgv) * 16 + (d & 15)) << 3) + e] = val;
+  }
+}
+
+// --------------------------------------------------------------------------
+// Shared tile arithmetic: scores of one 32-slot tile for one column block, and
+// the online-softmax step that turns them into the bf16 P operand.
+// --------------------------------------------------------------------------
+
+// x[0..3]: tokens 4*kg+r of block 0, x[4..7]: tokens 16+4*kg+r (already scaled to
+// log2 units and masked with -inf).  Updates (m, l), returns P and the factor the
+// running output must be multiplied by.
+__device__ __forceinline__ bf16x8 softmax_step(const float (&x)[8], float &m, float &l, float &alpha) {
+  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  mx = fmaxf(mx, xor_lanes(mx, 16));
+  mx = fmaxf(mx, xor_lanes(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  const float m_safe = (m_new == ZZ_NEG_INF) ? 0.f : m_new;  // a column with nothing visible yet
+  alpha = fast_exp2(m - m_safe);
+  bf16x8 P;
+  float sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const __bf16 pb = (__bf16)fast_exp2(x[e] - m_safe);
+    P[e] = pb;
+    sum += (float)pb;  // normalise by what is actually multiplied into V
+  }
+  l = l * alpha + sum;
+  m = m_new;
+  return P;
+}
+
+// --------------------------------------------------------------------------
+// Decode: split-K over the occupied slots of one (batch, kv head).
+// grid (n_splits, heads of the group, B), 4 waves per workgroup; wave w takes tiles
+// t0+w, t0+w+4, ... of the workgroup's range, double-buffered in registers.
+// --------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
+  constexpr int KS = D / 32;      // MFMA k-steps over the head dimension
+  constexpr int NL = D / 16;      // 1 KiB loads in the K part (= 2*KS) and in the V part
+  constexpr int TILE_U4 = 8 * D;  // uint4 per KV tile
+  constexpr int OP = D + 4;       // padded row of the cross-wave reduction buffer
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, kg = lane >> 4;
+  const int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  const int G = p.group_size;
+  const int g = p.heads[hg];
+
+  bf16x8 qop[KS];
+  {
+    const uint4 *qp = (const uint4 *)p.q + ((int64_t)b * p.n_q_heads + g * G + (col < G ? col : 0)) * (D / 8) + kg;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      uint4 v = qp[4 * s];
+      if (col >= G) v = make_uint4(0, 0, 0, 0);
+      qop[s] = as_bf16x8(v);
+    }
+  }
+
+  const uint4 *tiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4 + lane;
+  const int t0 = split * p.tiles_per_split;
+  const int t1 = min(t0 + p.tiles_per_split, p.n_tiles_valid);
+  const int last_tile = p.n_tiles_valid - 1;
+  const bool ragged = (p.n_valid & 31) != 0;
+
+  f32x4 acc[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = ZZ_NEG_INF, l = 0.f;
+
+  auto load_tile = [&](uint4(&kv)[2 * NL], int t) {
+    const uint4 *src = tiles + (int64_t)t * TILE_U4;
+#pragma unroll
+    for (int i = 0; i < 2 * NL; ++i) kv[i] = src[i * 64];
+  };
+
+  auto compute = [&](uint4(&kv)[2 * NL], int t) {
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[s]), qop[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[KS + s]), qop[s], s1, 0, 0, 0);
+    }
+    float x[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      x[r] = s0[r] * p.scale_log2e;
+      x[4 + r] = s1[r] * p.scale_log2e;
+    }
+    if (ragged && t == last_tile) {
+      // slots past n_valid were never written: no score, and their V bits (possibly
+      // NaN patterns) must not reach the accumulating MFMA
+      const int base = t * 32 + 4 * kg;
+      unsigned int keep[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (base + r >= p.n_valid) x[r] = ZZ_NEG_INF;
+        if (base + 16 + r >= p.n_valid) x[4 + r] = ZZ_NEG_INF;
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int s_lo = base + (w >= 2 ? 16 : 0) + 2 * (w & 1);
+        keep[w] = (s_lo < p.n_valid ? 0x0000ffffu : 0u) | (s_lo + 1 < p.n_valid ? 0xffff0000u : 0u);
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        kv[NL + i].x &= keep[0];
+        kv[NL + i].y &= keep[1];
+        kv[NL + i].z &= keep[2];
+        kv[NL + i].w &= keep[3];
+      }
+    }
+    float alpha;
+    const bf16x8 P = softmax_step(x, m, l, alpha);
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) acc[i] *= alpha;
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[NL + i]), P, acc[i], 0, 0, 0);
+  };
+
+  {
+    uint4 bufA[2 * NL], bufB[2 * NL];
+    int t = t0 + wave;
+    if (t < t1) load_tile(bufA, t);
+    for (; t < t1; t += 2 * ZZ_WAVES_PER_WG) {
+      const int tn = t + ZZ_WAVES_PER_WG;
+      if (tn < t1) load_tile(bufB, tn);
+      compute(bufA, t);
+      if (tn < t1) {
+        if (tn + ZZ_WAVES_PER_WG < t1) load_tile(bufA, tn + ZZ_WAVES_PER_WG);
+        compute(bufB, tn);
+      }
+    }
+  }
+
+  // ---- combine the four waves of the workgroup through LDS ----
+  __shared__ float s_o[ZZ_WAVES_PER_WG][16][OP];
+  __shared__ float s_m[ZZ_WAVES_PER_WG][16];
+  __shared__ float s_l[ZZ_WAVES_PER_WG][16];
+  float l_tot = l + xor_lanes(l, 16);
+  l_tot += xor_lanes(l_tot, 32);
+  if (col < G) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s_o[wave][col][16 * i + 4 * kg + r] = acc[i][r];
+    if (kg == 0) {
+      s_m[wave][col] = m;
+      s_l[wave][col] = l_tot;
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int c = idx / D, d = idx % D;
+    float M = ZZ_NEG_INF;
+#pragma unroll
+    for (int w = 0; w < ZZ_WAVES_PER_WG; ++w) M = fmaxf(M, s_m[w][c]);
+    const float Ms = (M == ZZ_NEG_INF) ? 0.f : M;
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < ZZ_WAVES_PER_WG; ++w) {
+      const float f = fast_exp2(s_m[w][c] - Ms);
+      L += s_l[w][c] * f;
+      O += s_o[w][c][d] * f;
+    }
+    const int h = g * G + c;
+    if (p.n_splits == 1) {
+      ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
+    } else {
+      const int64_t row = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS + split;
+      p.part_o[row * D + d] = O;
+      if (d == 0) {
+        p.part_ml[row * 2] = M;
+        p.part_ml[row * 2 + 1] = L;
+      }
+    }
+  }
+}
+
+// Cross-split log-sum-exp combine: grid (heads of the group * G, B), D threads.
+template <int D>
+__global__ __launch_bounds__(D) void zz_combine_kernel(zz_decode_params p) {
+  const int G = p.group_size;
+  const int h = p.heads[blockIdx.x / G] * G + blockIdx.x % G;
+  const int b = blockIdx.y, d = threadIdx.x;
+  const int64_t row0 = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS;
+  float M = ZZ_NEG_INF;
+  for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, p.part_ml[(row0 + s) * 2]);
+  float L = 0.f, O = 0.f;
+  for (int s = 0; s < p.n_splits; ++s) {
+    const float f = fast_exp2(p.part_ml[(row0 + s) * 2] - M);
+    L += p.part_ml[(row0 + s) * 2 + 1] * f;
+    O += p.part_o[(row0 + s) * D + d] * f;
+  }
+  ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
+}
+
+// --------------------------------------------------------------------------
+// Prefill: flash-style over KV tiles, columns = 16 query positions of one head.
+// A wave owns NB column blocks: Gc heads of the group x (NB/Gc) blocks of 16
+// consecutive query positions, so a loaded K/V tile is reused NB times.
+// grid (query blocks, heads of the group * head chunks, B), 4 waves.
+// Keys come from the cached tiles (positions < n_past) and then from the staged
+// chunk (position = n_past + index).  Tiles in which no key is visible to any of
+// the wave's queries are skipped without being loaded.
+// --------------------------------------------------------------------------
+template <int D, int NB>
+__global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
+  constexpr int KS = D / 32, NL = D / 16, TILE_U4 = 8 * D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, kg = lane >> 4;
+  const int G = p.group_size;
+  const int n_hchunks = G / Gc;
+  const int hg = blockIdx.y / n_hchunks, hc = blockIdx.y % n_hchunks;
+  const int b = blockIdx.z;
+  const int g = p.heads[hg];
+  const int QW = 16 * (NB / Gc);  // query positions per wave
+  const int iq0 = (blockIdx.x * ZZ_WAVES_PER_WG + wave) * QW;  // first query index of the wave
+  if (iq0 >= p.n_new) return;  // no barriers below: a wave may leave early
+  const int iq_last = min(iq0 + QW, p.n_new) - 1;
+  const int i_lo = p.n_past + iq0, i_hi = p.n_past + iq_last;
+  const bool streaming = p.grp.streaming != 0;
+  const int S = p.sink, W = p.window;
+
+  // per column block: head, query position, Q operand
+  int qpos[NB];
+  bf16x8 qop[NB][KS];
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb) {
+    const int h = g * G + hc * Gc + cb % Gc;
+    const int iq = iq0 + (cb / Gc) * 16 + col;
+    const bool ok = iq < p.n_new;
+    qpos[cb] = ok ? p.n_past + iq : -1;  // -1: nothing is visible, output not stored
+    const uint4 *qp = (const uint4 *)p.q + (((int64_t)b * p.n_new + (ok ? iq : 0)) * p.n_q_heads + h) * (D / 8) + kg;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qop[cb][s] = as_bf16x8(qp[4 * s]);
+  }
+
+  f32x4 acc[NB][NL];
+  float m[NB], l[NB];
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb) {
+    m[cb] = ZZ_NEG_INF;
+    l[cb] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) acc[cb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // One tile: pos[e] is the position of the lane's e-th token (e<4: slot 4kg+e,
+  // e>=4: slot 16+4kg+e-4), or -1 if that slot holds nothing.
+  auto process = [&](const uint4 *src, const int (&pos)[8]) {
+    uint4 kv[2 * NL];
+#pragma unroll
+    for (int i = 0; i < 2 * NL; ++i) kv[i] = src[i * 64];
+    bool any_hole = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) any_hole |= pos[e] < 0;
+    if (__any(any_hole)) {
+      unsigned int keep[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        keep[w] = (pos[2 * w] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * w + 1] >= 0 ? 0xffff0000u : 0u);
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        kv[NL + i].x &= keep[0];
+        kv[NL + i].y &= keep[1];
+        kv[NL + i].z &= keep[2];
+        kv[NL + i].w &= keep[3];
+      }
+    }
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[s]), qop[cb][s], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[KS + s]), qop[cb][s], s1, 0, 0, 0);
+      }
+      float x[8];
+      const int i = qpos[cb];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int j = pos[e];
+        const bool vis = (j >= 0) && (j <= i) && (!streaming || j < S || i - j < W);
+        const float sc = (e < 4 ? s0[e & 3] : s1[e & 3]) * p.scale_log2e;
+        x[e] = vis ? sc : ZZ_NEG_INF;
+      }
+      float alpha;
+      const bf16x8 P = softmax_step(x, m[cb], l[cb], alpha);
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int k = 0; k < NL; ++k) acc[cb][k] *= alpha;
+      }
+#pragma unroll
+      for (int k = 0; k < NL; ++k)
+        acc[cb][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[NL + k]), P, acc[cb][k], 0, 0, 0);
+    }
+  };
+
+  // does any of this lane's tokens matter to any query of the wave?
+  auto lane_needed = [&](const int (&pos)[8]) {
+    bool need = false;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int j = pos[e];
+      need |= (j >= 0) && (j <= i_hi) && (!streaming || j < S || j > i_lo - W);
+    }
+    return need;
+  };
+
+  // ---- cached tiles ----
+  {
+    const int occ = streaming ? min(p.n_past, S + W) : p.n_past;
+    const int n_ct = (occ + 31) / 32;
+    const uint4 *ctiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4 + lane;
+    const int newest = p.n_past - 1 - S;  // ring offset of the newest cached token
+    for (int t = 0; t < n_ct; ++t) {
+      int pos[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int slot = t * 32 + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
+        int ps = -1;
+        if (slot < occ) {
+          if (!streaming || slot < S)
+            ps = slot;
+          else {
+            const int r = slot - S;
+            ps = S + r + W * ((newest - r) / W);
+          }
+        }
+        pos[e] = ps;
+      }
+      if (streaming && !__any(lane_needed(pos))) continue;
+      process(ctiles + (int64_t)t * TILE_U4, pos);
+    }
+  }
+  // ---- staged chunk tiles ----
+  {
+    const uint4 *stiles = (const uint4 *)p.stage + ((int64_t)b * p.n_kv_heads + g) * p.stage_tiles * TILE_U4 + lane;
+    const int k_hi = (i_hi - p.n_past) / 32;
+    auto staged = [&](int k) {
+      int pos[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int idx = k * 32 + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
+        pos[e] = idx < p.n_new ? p.n_past + idx : -1;
+      }
+      process(stiles + (int64_t)k * TILE_U4, pos);
+    };
+    int k = 0;
+    if (streaming) {
+      // sink tokens that arrive with this chunk, then jump to the window
+      const int k_sink_end = (p.n_past < S) ? min(k_hi, (S - 1 - p.n_past) / 32) + 1 : 0;
+      for (; k < k_sink_end; ++k) staged(k);
+      const int first_win = i_lo - W + 1 - p.n_past;  // chunk index of the oldest window token
+      if (first_win > 0) k = max(k, first_win / 32);
+    }
+    for (; k <= k_hi; ++k) staged(k);
+  }
+
+  // ---- normalise and store ----
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb) {
+    float lt = l[cb] + xor_lanes(l[cb], 16);
+    lt += xor_lanes(lt, 32);
+    if (qpos[cb] < 0) continue;
+    const float inv = 1.0f / lt;
+    const int h = g * G + hc * Gc + cb % Gc;
+    const int iq = qpos[cb] - p.n_past;
+    __bf16 *op = (__bf16 *)p.out + (((int64_t)b * p.n_new + iq) * p.n_q_heads + h) * D + 4 * kg;
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+      bf16x4 o;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][k][r] * inv);
+      *(bf16x4 *)(op + 16 * k) = o;
+    }
+  }
+}
+
+// --------------------------------------------------------------------------
+// Launchers
+// --------------------------------------------------------------------------
+
+// The launch's own status: hipGetLastError() would also report errors other runtime
+// calls of the caller (an event query that is not ready yet) left behind.
+template <typename P, typename... Extra>
+static hipError_t launch(void (*kernel)(P, Extra...), dim3 grid, dim3 block, hipStream_t s, P p, Extra... extra) {
+  void *args[] = {(void *)&p, (void *)&extra...};
+  return hipLaunchKernel((const void *)kernel, grid, block, args, 0, s);
+}
+
+int zz_query_num_cu() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return n;
+}
+
+hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s) {
+  const int64_t total = (int64_t)p.batch * p.n_new * p.n_kv_heads * (p.head_dim / 8);
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  if (p.head_dim == 128) return launch(zz_append_kernel<128>, dim3(blocks), dim3(256), s, p);
+  return launch(zz_append_kernel<64>, dim3(blocks), dim3(256), s, p);
+}
+
+hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
+  // staging is an append of the chunk into an empty, never-evicting cache of its own
+  zz_append_params p = {};
+  p.k_new = sp.k_new;
+  p.v_new = sp.v_new;
+  p.grp[0].base = sp.stage;
+  p.grp[0].n_heads = sp.n_kv_heads;
+  p.grp[0].n_tiles = sp.stage_tiles;
+  p.grp[0].streaming = 0;
+  for (int g = 0; g < sp.n_kv_heads; ++g) {
+    p.head_group[g] = 0;
+    p.head_index[g] = (uint8_t)g;
+  }
+  p.len = 0;
+  p.n_new = sp.n_new;
+  p.batch = sp.batch;
+  p.n_kv_heads = sp.n_kv_heads;
+  p.head_dim = sp.head_dim;
+  p.sink = 0;
+  p.window = 1;
+  return zz_launch_append(p, s);
+}
+
+hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
+  const dim3 grid(p.n_splits, p.grp.n_heads, p.batch);
+  hipError_t e = p.head_dim == 128 ? launch(zz_decode_kernel<128>, grid, dim3(256), s, p)
+                                   : launch(zz_decode_kernel<64>, grid, dim3(256), s, p);
+  if (e != hipSuccess || p.n_splits == 1) return e;
+  const dim3 cgrid(p.grp.n_heads * p.group_size, p.batch);
+  if (p.head_dim == 128) return launch(zz_combine_kernel<128>, cgrid, dim3(128), s, p);
+  return launch(zz_combine_kernel<64>, cgrid, dim3(64), s, p);
+}
+
+hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {
+  constexpr int NB = 4;
+  const int G = p.group_size;
+  const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;  // heads per wave, must divide NB
+  const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
+  const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
+  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, Gc);
+  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, Gc);
+}

@@ -1,0 +1,211 @@
+"""Host side of the C ABI, without a GPU: the library loads and exports every
+declared symbol, configs are validated, the arena layout and the slot rule are
+what include/zz.h documents, and every error path returns its code before any
+launch."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import zz_inputs
+from oracle import zz_oracle as O
+from paper_2508_12407_amd import binding as zb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+E = zb.ERR
+FAKE_ARENA, FAKE_WS = 0x10000000, 0x20000000   # never dereferenced: failing calls launch nothing
+
+
+def mk(L=2, Hq=4, Hkv=2, D=64, B=1, max_ctx=1100, S=16, W=64, chunk=1024, layout=zb.ZZ_ZIGZAG, lmask=(0, 1),
+       hmask=None, scale=0.0):
+    return zb.make_config(L, Hq, Hkv, D, B, max_ctx, S, W, chunk, layout, scale,
+                          None if lmask is None else np.array(lmask, np.uint8),
+                          None if hmask is None else np.array(hmask, np.uint8))
+
+
+def fake_ctx(cfg, keep):
+    return zb.Context(cfg, FAKE_ARENA, FAKE_WS, arena_nbytes=zb.arena_bytes(cfg),
+                      workspace_nbytes=zb.workspace_bytes(cfg), keep=keep)
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "zz.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(zz_[a-z_]+)\s*\(", hdr)))
+    assert {"zz_kv_append", "zz_attn_prefill", "zz_attn_decode", "zz_create", "zz_slot_of"} <= set(names)
+    raw = ctypes.CDLL(zb.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+
+
+def test_config_validation_codes():
+    def create(cfg):
+        h = ctypes.c_void_p()
+        return zb.lib.zz_create(ctypes.byref(cfg), FAKE_ARENA, 1 << 40, FAKE_WS, 1 << 40, ctypes.byref(h)), h
+
+    ok, keep = mk()
+    rc, h = create(ok)
+    assert rc == 0 and zb.lib.zz_destroy(h) == 0
+    bad = [
+        (dict(L=0), E["EINVAL"]), (dict(B=0), E["EINVAL"]), (dict(W=0), E["EINVAL"]), (dict(S=-1), E["EINVAL"]),
+        (dict(max_ctx=0), E["EINVAL"]), (dict(Hq=5), E["EINVAL"]), (dict(D=96), E["EUNSUPPORTED"]),
+        (dict(Hq=34, Hkv=2), E["EUNSUPPORTED"]), (dict(Hq=128, Hkv=128), E["EUNSUPPORTED"]),
+        (dict(layout=7), E["EINVAL"]), (dict(scale=-1.0), E["EINVAL"]), (dict(scale=float("nan")), E["EINVAL"]),
+        (dict(lmask=None), E["ESTATE"]),                                   # zigzag needs the layer mask
+        (dict(layout=zb.ZZ_MIXED, lmask=(0, 1), hmask=None), E["ESTATE"]),  # mixed needs the head mask
+    ]
+    for kw, code in bad:
+        cfg, keep = mk(**kw)
+        rc, _ = create(cfg)
+        assert rc == code, (kw, rc)
+        assert zb.arena_bytes(cfg) == 0 and zb.workspace_bytes(cfg) == 0
+    cfg, keep = mk()
+    h = ctypes.c_void_p()
+    assert zb.lib.zz_create(ctypes.byref(cfg), None, 1 << 40, FAKE_WS, 1 << 40, ctypes.byref(h)) == E["EINVAL"]
+    assert zb.lib.zz_create(ctypes.byref(cfg), FAKE_ARENA + 16, 1 << 40, FAKE_WS, 1 << 40, ctypes.byref(h)) == E["EALIGN"]
+    assert zb.lib.zz_create(ctypes.byref(cfg), FAKE_ARENA, zb.arena_bytes(cfg) - 1, FAKE_WS, 1 << 40, ctypes.byref(h)) == E["ENOSPC"]
+    assert zb.lib.zz_create(ctypes.byref(cfg), FAKE_ARENA, 1 << 40, FAKE_WS, zb.workspace_bytes(cfg) - 1, ctypes.byref(h)) == E["ENOSPC"]
+    assert zb.lib.zz_create(ctypes.byref(cfg), FAKE_ARENA, 1 << 40, FAKE_WS, 1 << 40, None) == E["EINVAL"]
+    assert zb.lib.zz_create(None, FAKE_ARENA, 1 << 40, FAKE_WS, 1 << 40, ctypes.byref(h)) == E["EINVAL"]
+    for code in E.values():
+        assert len(zb.strerror(code)) > 1
+    assert "unknown" in zb.strerror(-99)
+
+
+def test_streaming_cache_size_is_constant_in_context():
+    """Section 1: a streaming head waives all KV but sink + window."""
+    sizes = []
+    for max_ctx in (1024, 32768, 131072):
+        allS, k1 = mk(L=1, Hq=32, Hkv=8, D=128, max_ctx=max_ctx, S=64, W=256, lmask=(1,))
+        allR, k2 = mk(L=1, Hq=32, Hkv=8, D=128, max_ctx=max_ctx, S=64, W=256, lmask=(0,))
+        sizes.append(zb.arena_bytes(allS))
+        assert zb.arena_bytes(allR) == 2 * 8 * max_ctx * 128 * 2
+    assert sizes[0] == sizes[1] == sizes[2] == 2 * 8 * 320 * 128 * 2
+
+
+def test_zigzag_and_mixed_have_the_same_kv_budget():
+    """Section 2.2: p/L equals the head sparsity, so both layouts hold the same bytes."""
+    w = zz_inputs.WORKLOADS["c3_llama8b_128k_b4"]
+    lm = zz_inputs.draw_layer_mask(0, w.n_layers, w.n_streaming_layers)
+    hm = zz_inputs.draw_kvhead_mask(0, w.n_layers, w.n_kv_heads, w.n_kv_heads // 2)
+    zig, k1 = zb.make_config(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.context, w.sink, w.window,
+                             0, zb.ZZ_ZIGZAG, 0.0, lm, None)
+    mix, k2 = zb.make_config(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.context, w.sink, w.window,
+                             0, zb.ZZ_MIXED, 0.0, None, hm)
+    assert zb.arena_bytes(zig) == zb.arena_bytes(mix) == 16 * 4 * (2147483648 // 4 + 5242880 // 4)
+    cz, cm = fake_ctx(zig, k1), fake_ctx(mix, k2)
+    assert [cz.layer_launches(l) for l in range(32)] == [1] * 32      # one attention per layer
+    assert [cm.layer_launches(l) for l in range(32)] == [2] * 32      # two per layer when kinds mix
+
+
+@pytest.mark.parametrize("S,W", [(16, 64), (0, 5), (3, 1), (64, 256)])
+def test_slot_of_matches_oracle_cache_model(S, W):
+    cfg, keep = mk(S=S, W=W, max_ctx=5000)
+    for pos in list(range(0, 3 * (S + W) + 5)) + [4999]:
+        assert zb.slot_of(cfg, 0, 0, pos) == pos                              # layer 0: retrieval
+        s = zb.slot_of(cfg, 1, 1, pos)                                        # layer 1: streaming
+        assert 0 <= s < S + W
+        assert O.slot_position(s, pos + 1, True, S, W) == pos                 # newest token sits in its slot
+    assert zb.slot_of(cfg, 0, 0, 5000) == E["ERANGE"]
+    assert zb.slot_of(cfg, 1, 0, 10 ** 9) >= 0
+    assert zb.slot_of(cfg, 2, 0, 0) == E["ERANGE"] and zb.slot_of(cfg, 0, 2, 0) == E["ERANGE"]
+    assert zb.slot_of(cfg, 0, 0, -1) == E["ERANGE"]
+
+
+def doc_elem_index(which, t, d, D):
+    """The tile formula as include/zz.h words it, typed independently of the library."""
+    if which == 0:
+        return ((t // 16) * (D // 8) + d // 8) * 128 + (t % 16) * 8 + d % 8
+    return 32 * D + ((d // 16) * 4 + (t % 16) // 4) * 128 + (d % 16) * 8 + 4 * (t // 16) + t % 4
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_arena_offsets_follow_documented_layout_and_never_collide(D):
+    hm = np.array([[0, 1, 1, 0], [1, 0, 0, 0]], np.uint8)
+    cfg, keep = zb.make_config(2, 8, 4, D, 2, 100, 5, 40, 0, zb.ZZ_MIXED, 0.0, None, hm)
+    ctx = fake_ctx(cfg, keep)
+    tile_bytes = 128 * D
+    seen = set()
+    regions = []   # (layer, kind) in arena order: retrieval heads first, then streaming
+    base = 0
+    for l in range(2):
+        for kind in (0, 1):
+            heads = [g for g in range(4) if hm[l, g] == kind]
+            cap = 45 if kind else 100
+            n_tiles = -(-cap // 32)
+            for b in range(2):
+                for hi, g in enumerate(heads):
+                    for slot in range(cap):
+                        for which in (0, 1):
+                            for d in (0, 1, 7, 8, 15, 16, D - 1):
+                                want = base + ((b * len(heads) + hi) * n_tiles + slot // 32) * tile_bytes \
+                                    + 2 * doc_elem_index(which, slot % 32, d, D)
+                                got = ctx.kv_elem_offset(l, which, b, g, slot, d)
+                                assert got == want, (l, kind, b, g, slot, which, d)
+                                assert got not in seen
+                                seen.add(got)
+            base += 2 * len(heads) * n_tiles * tile_bytes
+            base = -(-base // 256) * 256
+    assert base == zb.arena_bytes(cfg)
+    # inside one tile the map (which, t, d) -> element is a bijection onto the tile
+    idx = sorted(doc_elem_index(w, t, d, D) for w in (0, 1) for t in range(32) for d in range(D))
+    assert idx == list(range(64 * D))
+    assert ctx.kv_elem_offset(0, 0, 0, 0, 100, 0) == E["ERANGE"]     # retrieval head: slot >= max_ctx
+    assert ctx.kv_elem_offset(0, 0, 0, 1, 45, 0) == E["ERANGE"]      # streaming head: slot >= S + W
+    assert ctx.kv_elem_offset(0, 2, 0, 0, 0, 0) == E["EINVAL"]
+
+
+def test_entry_point_error_paths_launch_nothing():
+    cfg, keep = mk()
+    ctx = fake_ctx(cfg, keep)
+    h = ctx._h
+    A = 0x30000000   # aligned fake tensor address
+    L = zb.lib
+    assert L.zz_attn_decode(h, 0, A, A, None) == E["ESTATE"]                 # empty layer
+    assert L.zz_kv_append(h, 0, A, A, 0, None) == 0                          # n_new == 0: no-op
+    assert L.zz_attn_prefill(h, 0, A, A, A, 0, A, None) == 0
+    assert L.zz_kv_append(h, 0, None, None, 0, None) == 0
+    assert L.zz_kv_append(h, 2, A, A, 1, None) == E["ERANGE"]
+    assert L.zz_kv_append(h, -1, A, A, 1, None) == E["ERANGE"]
+    assert L.zz_kv_append(h, 0, A, A, -1, None) == E["ERANGE"]
+    assert L.zz_kv_append(h, 0, None, A, 1, None) == E["EINVAL"]
+    assert L.zz_kv_append(h, 0, A + 2, A, 1, None) == E["EALIGN"]
+    assert L.zz_kv_append(None, 0, A, A, 1, None) == E["EINVAL"]
+    assert L.zz_attn_decode(h, 5, A, A, None) == E["ERANGE"]
+    assert L.zz_attn_decode(h, 0, None, A, None) == E["EINVAL"]
+    assert L.zz_attn_decode(h, 0, A, A + 8, None) == E["EALIGN"]
+    assert L.zz_attn_prefill(h, 0, A, A, A, 1025, A, None) == E["ERANGE"]    # > max_chunk
+    assert L.zz_attn_prefill(h, 0, A, A, A, -3, A, None) == E["ERANGE"]
+    assert L.zz_attn_prefill(h, 0, A, None, A, 4, A, None) == E["EINVAL"]
+    assert L.zz_attn_prefill(h, 0, A, A, A + 4, 4, A, None) == E["EALIGN"]
+    assert L.zz_attn_prefill(h, 9, A, A, A, 4, A, None) == E["ERANGE"]
+    # capacity: lengths are bounded by max_ctx
+    assert L.zz_set_layer_len(h, 0, 1099) == 0 and ctx.layer_len(0) == 1099
+    assert L.zz_kv_append(h, 0, A, A, 2, None) == E["ENOSPC"] and ctx.layer_len(0) == 1099
+    assert L.zz_attn_prefill(h, 0, A, A, A, 2, A, None) == E["ENOSPC"]
+    assert L.zz_set_layer_len(h, 0, 1101) == E["ERANGE"] and L.zz_set_layer_len(h, 0, -1) == E["ERANGE"]
+    assert ctx.layer_len(7) == E["ERANGE"] and ctx.layer_launches(7) == E["ERANGE"]
+    assert L.zz_reset(h) == 0 and ctx.layer_len(0) == 0
+    assert L.zz_tune(h, 99, 1) == E["EINVAL"] and L.zz_tune(h, zb.TUNE_DECODE_SPLITS, 129) == E["ERANGE"]
+    assert L.zz_reset(None) == E["EINVAL"] and L.zz_destroy(None) == E["EINVAL"]
+
+
+def test_decode_plan_fills_the_chip_and_respects_limits():
+    w = zz_inputs.WORKLOADS["c3_llama8b_128k_b4"]
+    lm = zz_inputs.draw_layer_mask(0, 32, 16)
+    cfg, keep = zb.make_config(32, 32, 8, 128, 4, w.context, 64, 256, 0, zb.ZZ_ZIGZAG, 0.0, lm, None)
+    ctx = fake_ctx(cfg, keep)
+    ctx.tune(zb.TUNE_NUM_CU, 256)
+    r = int(np.flatnonzero(lm == 0)[0]); s = int(np.flatnonzero(lm == 1)[0])
+    assert ctx.decode_plan(r, 0) == (0, 0)                                    # empty layer
+    ctx.set_layer_len(r, w.context); ctx.set_layer_len(s, w.context)
+    ns, tps = ctx.decode_plan(r, 0)
+    assert ns * 32 >= 2 * 256 and ns <= zb.ZZ_MAX_SPLITS and ns * tps >= w.context // 32 > (ns - 1) * tps
+    assert ctx.decode_plan(r, 1) == (0, 0)                                    # no streaming heads here
+    ns, tps = ctx.decode_plan(s, 1)
+    assert ns * tps >= 10 > (ns - 1) * tps and tps >= 4                       # 320 slots = 10 tiles
+    ctx.tune(zb.TUNE_DECODE_SPLITS, 128)
+    ns, tps = ctx.decode_plan(r, 0)
+    assert ns == 128 and tps == 32
