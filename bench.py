@@ -1,0 +1,331 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZigzagAttention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: for every layer, append
+the new token's K/V (ring evict in streaming layers) and run that layer's single
+attention launch.  Prints ONE JSON line (see the design doc for every field).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+ALIASES = {"c2": "c2_llama8b_32k_b1", "c3": "c3_llama8b_128k_b4", "c5": "c5_mha7b_32k_b8", "c4": "c4_prefill_64k"}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-mixed", action="store_true", help="skip the mixed-head layout comparison")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline and parity sample")
+    ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay of the step")
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--splits", type=int, default=0)
+    return ap.parse_args()
+
+
+def layer_bytes(w, streaming, n_ctx):
+    n_valid = min(n_ctx, w.sink + w.window) if streaming else n_ctx
+    return 2 * w.batch * w.n_kv_heads * n_valid * w.head_dim * 2
+
+
+class DecodeRun:
+    """One layout of one decode workload, resident in HBM."""
+
+    def __init__(self, w, layout, seed, args, fill="append", sample=()):
+        import torch
+        import zz_inputs
+        from paper_2508_12407_amd import binding as zb, harness
+        self.torch, self.zb, self.w = torch, zb, w
+        self.lmask = zz_inputs.draw_layer_mask(seed, w.n_layers, w.n_streaming_layers)
+        kw = {}
+        if layout == "zigzag":
+            kw = dict(layout=zb.ZZ_ZIGZAG, layer_is_streaming=self.lmask)
+        else:
+            frac = w.n_streaming_layers / w.n_layers
+            per_layer = int(round(frac * w.n_kv_heads))
+            self.hmask = zz_inputs.draw_kvhead_mask(seed, w.n_layers, w.n_kv_heads, per_layer)
+            kw = dict(layout=zb.ZZ_MIXED, kvhead_is_streaming=self.hmask)
+        self.layout = layout
+        self.N = w.context
+        self.st = harness.Stack(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, self.N, w.sink, w.window,
+                                **kw)
+        if args.wg_per_cu:
+            self.st.ctx.tune(zb.TUNE_DECODE_WG_PER_CU, args.wg_per_cu)
+        if args.splits:
+            self.st.ctx.tune(zb.TUNE_DECODE_SPLITS, args.splits)
+        gen = torch.Generator(device="cuda").manual_seed(seed + 1)
+        B, Hq, Hkv, D, L = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_layers
+        self.kept = {}
+        n_pre = self.N - 1
+        if fill == "append":
+            # the measured cache is one the library built: N-1 tokens appended in chunks
+            chunk = 8192
+            for l in range(L):
+                streaming = layout == "zigzag" and bool(self.lmask[l])
+                # a streaming layer keeps the sink tokens and the newest W: appending the first
+                # chunk and the last one (positions in between skipped) builds the same cache
+                starts = list(range(0, n_pre, chunk))
+                if streaming and len(starts) > 2:
+                    starts = [0, n_pre - chunk]
+                for a in starts:
+                    n = min(chunk, n_pre - a)
+                    self.st.ctx.set_layer_len(l, a)
+                    kc = torch.randn((B, n, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                    vc = torch.randn((B, n, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                    self.st.append(l, kc, vc)
+                    for (sl, b, g) in sample:
+                        if sl == l:
+                            self.kept.setdefault((sl, b, g), []).append(
+                                (a, kc[b, :, g].float().cpu().numpy(), vc[b, :, g].float().cpu().numpy()))
+        else:
+            # any bit pattern of the arena is some cache (the tile layout is a bijection):
+            # draw it directly, N(0,1) in bf16, and declare the lengths
+            view = self.st.arena.view(torch.bfloat16)
+            step = 1 << 28
+            for a in range(0, view.numel(), step):
+                n = min(step, view.numel() - a)
+                view[a:a + n] = torch.randn(n, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            for l in range(L):
+                self.st.ctx.set_layer_len(l, n_pre)
+        self.q = torch.randn((L, B, Hq, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        self.k1 = torch.randn((L, B, 1, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        self.v1 = torch.randn((L, B, 1, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        self.out = torch.empty_like(self.q)
+        torch.cuda.synchronize()
+
+    def step(self, attention_only=False):
+        st, ctx = self.st, self.st.ctx
+        sp = st.stream_ptr()
+        n_pre = self.N - 1
+        for l in range(self.w.n_layers):
+            if not attention_only:
+                ctx.set_layer_len(l, n_pre)
+                ctx.kv_append(l, self.k1[l], self.v1[l], 1, sp)
+            ctx.attn_decode(l, self.q[l], self.out[l], sp)
+
+    def timed(self, steps, warmup, attention_only=False):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(attention_only)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(attention_only)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def timed_graph(self, steps, warmup):
+        """The same step captured once into a HIP graph and replayed."""
+        torch = self.torch
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            self.step()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.step()
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def time_retrieval_launch(self, reps):
+        """Average duration of the attention launch of a retrieval layer (the dominant
+        kernel), HIP events on the launch stream."""
+        torch = self.torch
+        if self.layout != "zigzag":
+            return None
+        layers = [l for l in range(self.w.n_layers) if not self.lmask[l]]
+        if not layers:
+            return None
+        sp = self.st.stream_ptr()
+        evs = []
+        for r in range(reps + 1):
+            for l in layers:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                self.st.ctx.attn_decode(l, self.q[l], self.out[l], sp)
+                e1.record()
+                if r:
+                    evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = [a.elapsed_time(b) for a, b in evs]
+        return float(np.mean(ms)) * 1e-3
+
+    def bytes_per_step(self):
+        w = self.w
+        total = 0
+        for l in range(w.n_layers):
+            if self.layout == "zigzag":
+                total += layer_bytes(w, bool(self.lmask[l]), self.N)
+            else:
+                ns = int(self.hmask[l].sum())
+                total += layer_bytes(w, True, self.N) * ns // w.n_kv_heads
+                total += layer_bytes(w, False, self.N) * (w.n_kv_heads - ns) // w.n_kv_heads
+        return total
+
+
+def cpu_baseline_and_parity(run, seed):
+    """Times the fp64 oracle on a bounded sample of (layer, batch, kv head) units of the
+    same workload and checks the GPU output of those units against it."""
+    import torch
+    from oracle import zz_oracle as O
+    w = run.w
+    G = w.n_q_heads // w.n_kv_heads
+    scale = O.default_scale(w.head_dim)
+    qh = run.q.float().cpu().numpy()
+    k1 = run.k1.float().cpu().numpy()
+    v1 = run.v1.float().cpu().numpy()
+    out = run.out.float().cpu().numpy()
+    threads = min(os.cpu_count() or 1, 16)
+    units, meta = [], []
+    for (l, b, g), parts in run.kept.items():
+        streaming = bool(run.lmask[l])
+        pos = np.concatenate([np.arange(a, a + len(kc)) for (a, kc, vc) in parts] + [np.array([run.N - 1])])
+        K = np.concatenate([kc for (a, kc, vc) in parts] + [k1[l, b, :, g]])
+        V = np.concatenate([vc for (a, kc, vc) in parts] + [v1[l, b, :, g]])
+        J = O.attended_positions(run.N - 1, streaming, w.sink, w.window)
+        idx = np.searchsorted(pos, J)
+        assert np.array_equal(pos[idx], J), "a position the oracle attends to was never appended"
+        units.append((qh[l, b, g * G:(g + 1) * G], K[idx], V[idx]))
+        meta.append((l, b, g, streaming))
+    t0 = time.perf_counter()
+    res = O.decode_units(units, scale, threads=threads)
+    t_cpu = time.perf_counter() - t0
+    max_abs, num, den = 0.0, 0.0, 0.0
+    for (l, b, g, streaming), want in zip(meta, res):
+        got = out[l, b, g * G:(g + 1) * G].astype(np.float64)
+        max_abs = max(max_abs, float(np.abs(got - want).max()))
+        num += float(((got - want) ** 2).sum())
+        den += float((want ** 2).sum())
+    # extrapolate by unit count per layer kind
+    t_kind = {False: [], True: []}
+    for (l, b, g, streaming), u in zip(meta, units):
+        t1 = time.perf_counter()
+        O.decode_unit(u[0], u[1], u[2], scale)
+        t_kind[streaming].append(time.perf_counter() - t1)
+    n_units = {True: int(run.lmask.sum()) * w.batch * w.n_kv_heads,
+               False: int((1 - run.lmask).sum()) * w.batch * w.n_kv_heads}
+    serial = sum(np.mean(t_kind[k]) * n_units[k] for k in (False, True) if t_kind[k])
+    # measured parallel speed-up of the sample applied to the whole step
+    serial_sample = sum(sum(t_kind[k]) for k in (False, True))
+    speedup = serial_sample / t_cpu if t_cpu > 0 else 1.0
+    step_s = serial / max(speedup, 1.0)
+    return dict(value=step_s / w.batch * 1e6, unit="us/token", cores=threads, kind="oracle",
+                sample=f"{len(units)} (layer,batch,kv-head) units of this workload "
+                       f"({sum(1 for m in meta if not m[3])} retrieval, {sum(1 for m in meta if m[3])} streaming), "
+                       f"{t_cpu:.2f} s of oracle time on {threads} threads, extrapolated by unit count to the "
+                       f"{n_units[False] + n_units[True]} units of one step"), \
+        dict(max_abs=max_abs, rel_l2=float(np.sqrt(num / max(den, 1e-300))), units=len(units))
+
+
+def bench_decode(args, wname):
+    import torch
+    import zz_inputs
+    w = zz_inputs.WORKLOADS[wname]
+    lmask = zz_inputs.draw_layer_mask(args.seed, w.n_layers, w.n_streaming_layers)
+    retr = [l for l in range(w.n_layers) if not lmask[l]]
+    strm = [l for l in range(w.n_layers) if lmask[l]]
+    sample = []
+    if not args.no_cpu:
+        B, Hkv = w.batch, w.n_kv_heads
+        for l in retr[:2]:
+            sample += [(l, 0, 0), (l, B - 1, Hkv - 1)] + ([(l, B // 2, Hkv // 2)] if B * Hkv > 2 else [])
+        for l in strm[:2]:
+            sample += [(l, b, g) for b in sorted({0, B - 1}) for g in range(Hkv)]
+    run = DecodeRun(w, "zigzag", args.seed, args, fill="append", sample=sample)
+    t_step = run.timed(args.steps, args.warmup)
+    t_attn = run.timed(args.steps, args.warmup, attention_only=True)
+    t_graph = None if args.no_graph else run.timed_graph(args.steps, args.warmup)
+    t_launch = run.time_retrieval_launch(max(3, args.steps // 4))
+    nbytes = run.bytes_per_step()
+    cpu, parity = (None, None)
+    if not args.no_cpu:
+        run.step()
+        torch.cuda.synchronize()
+        cpu, parity = cpu_baseline_and_parity(run, args.seed)
+    ns, tps = run.st.ctx.decode_plan(retr[0], 0) if retr else (0, 0)
+    per_launch = layer_bytes(w, False, w.context)
+    out = {
+        "metric": "decode attention us/token (all layers)",
+        "value": t_step / w.batch * 1e6, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wname, "layout": "zigzag", "n_layers": w.n_layers, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "batch": w.batch, "context": w.context,
+                   "sink": w.sink, "window": w.window, "streaming_layers": w.n_streaming_layers,
+                   "launch": "plain stream launches, append + attention per layer",
+                   "retrieval_split_k": {"splits": ns, "tiles_per_split": tps}},
+        "achieved_GBps": nbytes / t_step / 1e9, "algorithmic_bytes_per_step": nbytes,
+        "attention_only": {"us_per_token": t_attn / w.batch * 1e6, "GBps": nbytes / t_attn / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "zz_decode_kernel<128> on one retrieval layer (+ its combine)",
+                     "achieved": per_launch / t_launch / 1e9 if t_launch else None, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": per_launch / t_launch / 1e9 / HBM_PEAK_GBPS if t_launch else None,
+                     "bytes_per_launch": per_launch, "avg_launch_us": t_launch * 1e6 if t_launch else None,
+                     "traffic": None},
+        "cpu_baseline": cpu, "parity_sample": parity,
+    }
+    if t_graph is not None:
+        out["hip_graph_replay"] = {"us_per_token": t_graph / w.batch * 1e6, "GBps": nbytes / t_graph / 1e9}
+    if not args.no_mixed:
+        del run
+        torch.cuda.empty_cache()
+        mixed = DecodeRun(w, "mixed", args.seed, args, fill="random")
+        tm = mixed.timed(args.steps, args.warmup)
+        tma = mixed.timed(args.steps, args.warmup, attention_only=True)
+        out["mixed_head_layout"] = {"us_per_token": tm / w.batch * 1e6, "ms_per_step": tm * 1e3,
+                                    "attention_only_us_per_token": tma / w.batch * 1e6,
+                                    "GBps": mixed.bytes_per_step() / tm / 1e9,
+                                    "algorithmic_bytes_per_step": mixed.bytes_per_step(),
+                                    "attention_launches_per_step": sum(mixed.st.ctx.layer_launches(l) for l in range(w.n_layers)),
+                                    "zigzag_speedup": tm / t_step, "zigzag_speedup_attention_only": tma / t_attn}
+        out["config"]["attention_launches_per_step"] = w.n_layers
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of the path); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    wname = ALIASES.get(args.workload, args.workload)
+    if wname == "c4_prefill_64k":
+        from bench_prefill import bench_prefill
+        out = bench_prefill(args, wname)
+    else:
+        out = bench_decode(args, wname)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

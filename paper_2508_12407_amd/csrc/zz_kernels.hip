@@ -28,6 +28,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// K/V of the cache are read once per launch and never again: a non-temporal load
+// keeps the stream from displacing anything in L2 / the memory-side cache and is
+// measurably faster on MI355X than a default-policy load for pure streaming.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4 *p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // --------------------------------------------------------------------------
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
   auto load_tile = [&](uint4(&kv)[2 * NL], int t) {
     const uint4 *src = tiles + (int64_t)t * TILE_U4;
 #pragma unroll
-    for (int i = 0; i < 2 * NL; ++i) kv[i] = src[i * 64];
+    for (int i = 0; i < 2 * NL; ++i) kv[i] = load_stream(src + i * 64);
   };
 
   auto compute = [&](uint4(&kv)[2 * NL], int t) {
