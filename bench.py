@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-mixed", action="store_true", help="skip the mixed-head layout comparison")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline and parity sample")
     ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay of the step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 byte counters by)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0)
     return ap.parse_args()
@@ -259,6 +261,13 @@ def bench_decode(args, wname):
         for l in strm[:2]:
             sample += [(l, b, g) for b in sorted({0, B - 1}) for g in range(Hkv)]
     run = DecodeRun(w, "zigzag", args.seed, args, fill="append", sample=sample)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     t_step = run.timed(args.steps, args.warmup)
     t_attn = run.timed(args.steps, args.warmup, attention_only=True)
     t_graph = None if args.no_graph else run.timed_graph(args.steps, args.warmup)

@@ -142,7 +142,7 @@ int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv
 
 /* Tuning knobs, for measurement.  key: */
 enum {
-  ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 2)  */
+  ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 1)  */
   ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
   ZZ_TUNE_NUM_CU = 3             /* override the detected compute-unit count               */
 };

@@ -31,7 +31,7 @@ struct Layer {
 struct Layout {
   std::vector<Layer> layers;
   size_t arena_bytes = 0;
-  size_t ws_part_o = 0, ws_part_ml = 0, ws_stage = 0, ws_bytes = 0;
+  size_t ws_part_o = 0, ws_part_ml = 0, ws_counters = 0, ws_stage = 0, ws_bytes = 0;
   int stage_tiles = 0;
 };
 
@@ -90,6 +90,8 @@ void build_layout(const zz_config *c, Layout *lo) {
   w += align_up((size_t)c->batch * c->n_q_heads * ZZ_MAX_SPLITS * c->head_dim * sizeof(float), 256);
   lo->ws_part_ml = w;
   w += align_up((size_t)c->batch * c->n_q_heads * ZZ_MAX_SPLITS * 2 * sizeof(float), 256);
+  lo->ws_counters = w;
+  w += align_up((size_t)c->batch * c->n_kv_heads * sizeof(int), 256);
   lo->ws_stage = w;
   lo->stage_tiles = (int)ceil_div(c->max_chunk, ZZ_TILE_SLOTS);
   w += align_up((size_t)c->batch * c->n_kv_heads * lo->stage_tiles * tile, 256);
@@ -111,8 +113,12 @@ struct zz_ctx {
   char *ws = nullptr;
   float scale = 0.f;
   int num_cu = 0;          // 0: not queried yet
-  int tune_wg_per_cu = 2;
+  // One workgroup (four waves, two 16 KiB tiles in flight each) per compute unit already
+  // saturates HBM; more resident workgroups only lengthen the memory queues, and with
+  // them the latency every workgroup pays for its first tile and for its merge.
+  int tune_wg_per_cu = 1;
   int tune_splits = 0;
+  bool counters_zeroed = false;  // split counters are cleared by the first decode call
 };
 
 namespace {
@@ -361,6 +367,12 @@ int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *strea
   if (L.len <= 0) return ZZ_ESTATE;
   const zz_config &c = ctx->cfg;
   const int cu = num_cu(ctx);
+  int *counters = (int *)(ctx->ws + ctx->lo.ws_counters);
+  if (!ctx->counters_zeroed) {
+    if (hipError_t e = zz_launch_zero(counters, c.batch * c.n_kv_heads, (hipStream_t)stream))
+      return hip_failed("counter clear kernel", e);
+    ctx->counters_zeroed = true;
+  }
   for (int k = 0; k < 2; ++k) {
     const Group &G = L.grp[k];
     if (G.n_heads == 0) continue;
@@ -372,6 +384,7 @@ int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *strea
     p.out = out;
     p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
     p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
+    p.counters = counters;
     p.n_valid = (int)occupied(ctx, G, L.len);
     p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
     plan_decode(ctx, cu, G, L.len, &p.n_splits, &p.tiles_per_split);

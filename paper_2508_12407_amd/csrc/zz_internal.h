@@ -38,6 +38,7 @@ struct zz_decode_params {
   void *out;                      // [B, Hq, D] bf16
   float *part_o;                  // [B, Hq, ZZ_MAX_SPLITS, D]
   float *part_ml;                 // [B, Hq, ZZ_MAX_SPLITS, 2]  (max in log2 units, sum)
+  int *counters;                  // [B, Hkv] workgroups of the unit that have finished; 0 between launches
   int32_t n_valid;                // occupied slots (prefix of the cache)
   int32_t n_tiles_valid;          // ceil(n_valid / 32)
   int32_t tiles_per_split, n_splits;
@@ -68,6 +69,7 @@ struct zz_stage_params {
 
 hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s);
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
+hipError_t zz_launch_zero(int *p, int n, hipStream_t s);
 hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s);
 int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable

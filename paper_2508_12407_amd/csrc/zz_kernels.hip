@@ -37,6 +37,17 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Split-K partials cross workgroups that may sit on different XCDs, whose L2s are not
+// coherent with each other for ordinary accesses.  Device-scope relaxed atomics go
+// straight to the device-coherent level (sc1), so neither side needs an L2-wide
+// write-back / invalidate fence (which costs far more than the whole merge).
+__device__ __forceinline__ void store_device_coherent(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_coherent(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // --------------------------------------------------------------------------
@@ -118,7 +129,9 @@ __device__ __forceinline__ bf16x8 softmax_step(const float (&x)[8], float &m, fl
 // --------------------------------------------------------------------------
 // Decode: split-K over the occupied slots of one (batch, kv head).
 // grid (n_splits, heads of the group, B), 4 waves per workgroup; wave w takes tiles
-// t0+w, t0+w+4, ... of the workgroup's range, double-buffered in registers.
+// t0+w, t0+w+4, ... of the workgroup's range, double-buffered in registers.  The
+// workgroup of a unit that finishes last merges the unit's partials, so a layer's
+// attention is one launch.
 // --------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
@@ -258,31 +271,50 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
       ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
     } else {
       const int64_t row = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS + split;
-      p.part_o[row * D + d] = O;
+      store_device_coherent(p.part_o + row * D + d, O);
       if (d == 0) {
-        p.part_ml[row * 2] = M;
-        p.part_ml[row * 2 + 1] = L;
+        store_device_coherent(p.part_ml + row * 2, M);
+        store_device_coherent(p.part_ml + row * 2 + 1, L);
       }
     }
   }
+  if (p.n_splits == 1) return;
+
+  // ---- cross-split log-sum-exp combine by whichever workgroup of the unit ends last ----
+  // The partial stores above are device-coherent; each wave waits until its own have
+  // completed (vmcnt reaches 0 only when the stores are acknowledged), the barrier
+  // collects the four waves, then one thread counts the workgroup in.  The
+  // workgroup that completes the count reads every partial of the unit back with
+  // device-coherent loads, writes the output and re-arms the counter.
+  __shared__ int s_is_last;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int *counter = p.counters + b * p.n_kv_heads + g;
+  if (threadIdx.x == 0)
+    s_is_last = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.n_splits - 1);
+  __syncthreads();
+  if (!s_is_last) return;
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int c = idx / D, d = idx % D;
+    const int h = g * G + c;
+    const int64_t row0 = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS;
+    float M = ZZ_NEG_INF;
+    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, load_device_coherent(p.part_ml + (row0 + s) * 2));
+    float L = 0.f, O = 0.f;
+    for (int s = 0; s < p.n_splits; ++s) {
+      const float f = fast_exp2(load_device_coherent(p.part_ml + (row0 + s) * 2) - M);
+      L += load_device_coherent(p.part_ml + (row0 + s) * 2 + 1) * f;
+      O += load_device_coherent(p.part_o + (row0 + s) * D + d) * f;
+    }
+    ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
+  }
+  if (threadIdx.x == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Cross-split log-sum-exp combine: grid (heads of the group * G, B), D threads.
-template <int D>
-__global__ __launch_bounds__(D) void zz_combine_kernel(zz_decode_params p) {
-  const int G = p.group_size;
-  const int h = p.heads[blockIdx.x / G] * G + blockIdx.x % G;
-  const int b = blockIdx.y, d = threadIdx.x;
-  const int64_t row0 = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS;
-  float M = ZZ_NEG_INF;
-  for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, p.part_ml[(row0 + s) * 2]);
-  float L = 0.f, O = 0.f;
-  for (int s = 0; s < p.n_splits; ++s) {
-    const float f = fast_exp2(p.part_ml[(row0 + s) * 2] - M);
-    L += p.part_ml[(row0 + s) * 2 + 1] * f;
-    O += p.part_o[(row0 + s) * D + d] * f;
-  }
-  ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
+// Zeroes the split counters once per context (the library never memsets caller memory).
+__global__ void zz_zero_kernel(int *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 // --------------------------------------------------------------------------
@@ -528,10 +560,11 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
   const dim3 grid(p.n_splits, p.grp.n_heads, p.batch);
   hipError_t e = p.head_dim == 128 ? launch(zz_decode_kernel<128>, grid, dim3(256), s, p)
                                    : launch(zz_decode_kernel<64>, grid, dim3(256), s, p);
-  if (e != hipSuccess || p.n_splits == 1) return e;
-  const dim3 cgrid(p.grp.n_heads * p.group_size, p.batch);
-  if (p.head_dim == 128) return launch(zz_combine_kernel<128>, cgrid, dim3(128), s, p);
-  return launch(zz_combine_kernel<64>, cgrid, dim3(64), s, p);
+  return e;
+}
+
+hipError_t zz_launch_zero(int *p, int n, hipStream_t s) {
+  return launch(zz_zero_kernel, dim3((n + 255) / 256), dim3(256), s, p, n);
 }
 
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {

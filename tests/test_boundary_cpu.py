@@ -202,7 +202,7 @@ def test_decode_plan_fills_the_chip_and_respects_limits():
     assert ctx.decode_plan(r, 0) == (0, 0)                                    # empty layer
     ctx.set_layer_len(r, w.context); ctx.set_layer_len(s, w.context)
     ns, tps = ctx.decode_plan(r, 0)
-    assert ns * 32 >= 2 * 256 and ns <= zb.ZZ_MAX_SPLITS and ns * tps >= w.context // 32 > (ns - 1) * tps
+    assert ns * 32 >= 256 and ns <= zb.ZZ_MAX_SPLITS and ns * tps >= w.context // 32 > (ns - 1) * tps
     assert ctx.decode_plan(r, 1) == (0, 0)                                    # no streaming heads here
     ns, tps = ctx.decode_plan(s, 1)
     assert ns * tps >= 10 > (ns - 1) * tps and tps >= 4                       # 320 slots = 10 tiles

@@ -116,6 +116,31 @@ def test_decode_llama_shape_ragged_tail_across_split_counts(streaming, splits):
     run_decode_case(2, 32, 8, 128, 64, 256, 3333, 7, streaming, splits=splits)
 
 
+def test_decode_split_merge_is_race_free_with_far_more_workgroups_than_cus():
+    """The workgroup that finishes last merges the split-K partials of its unit.  With
+    64 units x 128 splits (8192 workgroups) and fresh queries on every launch, a merge
+    that read a partial too early or stale would disagree with the unsplit result."""
+    H, zb = _harness()
+    B, Hq, Hkv, D, S, W, T = 8, 32, 8, 128, 64, 256, 4096
+    q, k, v = zz_inputs.make_qkv(61, B, T, Hq, Hkv, D)
+    st = H.Stack(1, Hq, Hkv, D, B, T, S, W, layer_is_streaming=[0], poison_arena=True)
+    st.append(0, H.to_dev_bf16(k), H.to_dev_bf16(v))
+    qs = H.to_dev_bf16(q[:, :60].transpose(1, 0, 2, 3).copy())          # 60 different query sets [60,B,Hq,D]
+    outs = {}
+    for splits in (1, 128):
+        st.ctx.tune(zb.TUNE_DECODE_SPLITS, splits)
+        assert st.ctx.decode_plan(0, 0)[0] == splits
+        o = torch.empty_like(qs)
+        for rep in range(3):
+            for i in range(qs.shape[0]):
+                st.decode(0, qs[i], o[i])
+        outs[splits] = H.from_dev(o)
+    for i in range(qs.shape[0]):
+        check(outs[128][i], outs[1][i], ("split merge", i))
+    want = O.decode_row(q[:, 7], k, v, T - 1, kinds_of(False, Hkv), S, W)
+    check(outs[128][7], want, "split merge vs oracle")
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 2), (32, 2), (6, 2)])
 def test_decode_group_sizes(Hq, Hkv):
     # G = 1 (MHA), 8, 16 (the widest column block) and a non-power-of-two group
