@@ -44,6 +44,19 @@ def parse():
     return ap.parse_args()
 
 
+def profiled_traffic(fname):
+    """HBM bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE / WRITE_SIZE
+    counters measured them (two --pmc runs, scaled by a known-size copy); the summary
+    of those runs is kept under profiles/.  None if there is no summary for the workload."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", fname)):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
+
+
 def layer_bytes(w, streaming, n_ctx):
     n_valid = min(n_ctx, w.sink + w.window) if streaming else n_ctx
     return 2 * w.batch * w.n_kv_heads * n_valid * w.head_dim * 2
@@ -94,10 +107,11 @@ class DecodeRun:
                     kc = torch.randn((B, n, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
                     vc = torch.randn((B, n, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
                     self.st.append(l, kc, vc)
-                    for (sl, b, g) in sample:
-                        if sl == l:
-                            self.kept.setdefault((sl, b, g), []).append(
-                                (a, kc[b, :, g].float().cpu().numpy(), vc[b, :, g].float().cpu().numpy()))
+                    if any(sl == l for (sl, _, _) in sample):
+                        kh, vh = kc.float().cpu().numpy(), vc.float().cpu().numpy()
+                        for (sl, b, g) in sample:
+                            if sl == l:
+                                self.kept.setdefault((sl, b, g), []).append((a, kh[b, :, g], vh[b, :, g]))
         else:
             # any bit pattern of the arena is some cache (the tile layout is a bijection):
             # draw it directly, N(0,1) in bf16, and declare the lengths
@@ -216,33 +230,34 @@ def cpu_baseline_and_parity(run, seed):
         assert np.array_equal(pos[idx], J), "a position the oracle attends to was never appended"
         units.append((qh[l, b, g * G:(g + 1) * G], K[idx], V[idx]))
         meta.append((l, b, g, streaming))
-    t0 = time.perf_counter()
-    res = O.decode_units(units, scale, threads=threads)
-    t_cpu = time.perf_counter() - t0
+    res = [None] * len(units)
+    t_kind, n_kind = {}, {}
+    for kind in (False, True):
+        ids = [i for i, mm in enumerate(meta) if mm[3] == kind]
+        if not ids:
+            continue
+        t0 = time.perf_counter()
+        outs = O.decode_units([units[i] for i in ids], scale, threads=threads)
+        t_kind[kind] = time.perf_counter() - t0
+        n_kind[kind] = len(ids)
+        for i, o in zip(ids, outs):
+            res[i] = o
     max_abs, num, den = 0.0, 0.0, 0.0
     for (l, b, g, streaming), want in zip(meta, res):
         got = out[l, b, g * G:(g + 1) * G].astype(np.float64)
         max_abs = max(max_abs, float(np.abs(got - want).max()))
         num += float(((got - want) ** 2).sum())
         den += float((want ** 2).sum())
-    # extrapolate by unit count per layer kind
-    t_kind = {False: [], True: []}
-    for (l, b, g, streaming), u in zip(meta, units):
-        t1 = time.perf_counter()
-        O.decode_unit(u[0], u[1], u[2], scale)
-        t_kind[streaming].append(time.perf_counter() - t1)
+    # extrapolate by unit count per layer kind (same thread count, same unit size)
     n_units = {True: int(run.lmask.sum()) * w.batch * w.n_kv_heads,
                False: int((1 - run.lmask).sum()) * w.batch * w.n_kv_heads}
-    serial = sum(np.mean(t_kind[k]) * n_units[k] for k in (False, True) if t_kind[k])
-    # measured parallel speed-up of the sample applied to the whole step
-    serial_sample = sum(sum(t_kind[k]) for k in (False, True))
-    speedup = serial_sample / t_cpu if t_cpu > 0 else 1.0
-    step_s = serial / max(speedup, 1.0)
+    step_s = sum(t_kind[k] / n_kind[k] * n_units[k] for k in t_kind)
+    t_cpu = sum(t_kind.values())
     return dict(value=step_s / w.batch * 1e6, unit="us/token", cores=threads, kind="oracle",
                 sample=f"{len(units)} (layer,batch,kv-head) units of this workload "
-                       f"({sum(1 for m in meta if not m[3])} retrieval, {sum(1 for m in meta if m[3])} streaming), "
-                       f"{t_cpu:.2f} s of oracle time on {threads} threads, extrapolated by unit count to the "
-                       f"{n_units[False] + n_units[True]} units of one step"), \
+                       f"({n_kind.get(False, 0)} retrieval, {n_kind.get(True, 0)} streaming: every unit of the "
+                       f"sampled layers), {t_cpu:.2f} s wall on {threads} threads, extrapolated by unit count "
+                       f"to the {n_units[False] + n_units[True]} units of one step"), \
         dict(max_abs=max_abs, rel_l2=float(np.sqrt(num / max(den, 1e-300))), units=len(units))
 
 
@@ -255,11 +270,11 @@ def bench_decode(args, wname):
     strm = [l for l in range(w.n_layers) if lmask[l]]
     sample = []
     if not args.no_cpu:
+        # every (batch, kv head) unit of two retrieval and two streaming layers
         B, Hkv = w.batch, w.n_kv_heads
-        for l in retr[:2]:
-            sample += [(l, 0, 0), (l, B - 1, Hkv - 1)] + ([(l, B // 2, Hkv // 2)] if B * Hkv > 2 else [])
-        for l in strm[:2]:
-            sample += [(l, b, g) for b in sorted({0, B - 1}) for g in range(Hkv)]
+        n_r = 2 if B * Hkv <= 32 else 1
+        for l in retr[:n_r] + strm[:2]:
+            sample += [(l, b, g) for b in range(B) for g in range(Hkv)]
     run = DecodeRun(w, "zigzag", args.seed, args, fill="append", sample=sample)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
@@ -292,11 +307,11 @@ def bench_decode(args, wname):
                    "retrieval_split_k": {"splits": ns, "tiles_per_split": tps}},
         "achieved_GBps": nbytes / t_step / 1e9, "algorithmic_bytes_per_step": nbytes,
         "attention_only": {"us_per_token": t_attn / w.batch * 1e6, "GBps": nbytes / t_attn / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "zz_decode_kernel<128> on one retrieval layer (+ its combine)",
+        "roofline": {"bound": "hbm", "kernel": "zz_decode_kernel<128>, one retrieval layer (split-K merge included)",
                      "achieved": per_launch / t_launch / 1e9 if t_launch else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": per_launch / t_launch / 1e9 / HBM_PEAK_GBPS if t_launch else None,
                      "bytes_per_launch": per_launch, "avg_launch_us": t_launch * 1e6 if t_launch else None,
-                     "traffic": None},
+                     "traffic": profiled_traffic("decode_retrieval_%s.txt" % wname)},
         "cpu_baseline": cpu, "parity_sample": parity,
     }
     if t_graph is not None:
