@@ -59,6 +59,7 @@ def _load():
         "zz_kv_elem_offset": (I64, [V, I, I, I, I, I64, I]),
         "zz_tune": (I, [V, I, I]),
         "zz_decode_plan": (I, [V, I, I, P(I), P(I)]),
+        "zz_prefill_tile_counts": (I, [V, I, I, P(I64), P(I64)]),
         "zz_strerror": (C.c_char_p, [I]),
         "zz_last_error_detail": (C.c_char_p, []),
     }
@@ -163,6 +164,11 @@ class Context:
 
     def kv_elem_offset(self, layer, which, b, kv_head, slot, d):
         return int(lib.zz_kv_elem_offset(self._h, layer, which, b, kv_head, slot, d))
+
+    def prefill_tile_counts(self, layer, n_new):
+        a, b = C.c_int64(), C.c_int64()
+        self._chk(lib.zz_prefill_tile_counts(self._h, layer, n_new, C.byref(a), C.byref(b)), "zz_prefill_tile_counts")
+        return a.value, b.value
 
     def tune(self, key, value):
         self._chk(lib.zz_tune(self._h, key, value), "zz_tune")
