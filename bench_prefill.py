@@ -131,8 +131,8 @@ def bench_prefill(args, wname):
                    "head_dim": D, "batch": B, "prompt": T, "chunk": C, "sink": w.sink, "window": w.window,
                    "streaming_layers": w.n_streaming_layers, "step": "whole prompt: attention + append per chunk per layer"},
         "algorithmic_flop_per_step": flop, "us_per_prompt_token": t_step / (T * B) * 1e6,
-        "skipped_tile_fraction": 1.0 - vis / cau, "tile": "32 keys x 16 query positions (x4 heads of the KV group)",
-        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128,4>, retrieval layer, last 4096-token chunk of 65536",
+        "skipped_tile_fraction": 1.0 - vis / cau, "tile": "32 keys x 64 query positions (x4 heads of the KV group)",
+        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128,4,3>, retrieval layer, last 4096-token chunk of 65536",
                      "achieved": flop_last / t_kernel / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_last / t_kernel / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop_per_launch": flop_last,
                      "avg_launch_us": t_kernel * 1e6, "traffic": None},

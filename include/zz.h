@@ -152,10 +152,10 @@ int zz_tune(zz_ctx *ctx, int key, int value);
  * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty. */
 int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
 
-/* Pure host arithmetic: how many (wavefront, 32-key tile) visits the next
+/* Pure host arithmetic: how many (workgroup, 32-key tile) visits the next
  * zz_attn_prefill(layer, n_new) performs, and how many a kernel that skipped
  * nothing below the causal diagonal would perform at the same granularity
- * (a wavefront covers 16, 32 or 64 consecutive query positions for group sizes
+ * (a workgroup covers 64, 128 or 256 consecutive query positions for group sizes
  * that are multiples of 4, of 2, or odd).  1 - visited/causal is the skipped-tile
  * fraction that the sink + window mask of streaming heads allows (Section 3.3). */
 int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *visited, int64_t *causal);

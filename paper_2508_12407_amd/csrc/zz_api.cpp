@@ -458,47 +458,31 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
   const int64_t n_past = L.len, S = c.sink, W = c.window;
   const int G = c.n_q_heads / c.n_kv_heads;
   const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  const int QW = 16 * (4 / Gc);  // query positions per wave, as zz_launch_prefill chooses them
+  const int QB = ZZ_WAVES_PER_WG * 16 * (4 / Gc);  // query positions per workgroup, as zz_launch_prefill chooses them
   int64_t vis = 0, cau = 0;
   for (int k = 0; k < 2; ++k) {
     const Group &Gr = L.grp[k];
     if (Gr.n_heads == 0) continue;
-    const int64_t waves_per_range = (int64_t)c.batch * Gr.n_heads * (G / Gc);
-    const int64_t occ = occupied(ctx, Gr, n_past);
-    const int64_t n_ct = ceil_div(occ, ZZ_TILE_SLOTS);
-    for (int64_t iq0 = 0; iq0 < n_new; iq0 += QW) {
-      const int64_t iq_last = (iq0 + QW < n_new ? iq0 + QW : n_new) - 1;
-      const int64_t i_lo = n_past + iq0, i_hi = n_past + iq_last, k_hi = iq_last / ZZ_TILE_SLOTS;
-      // the causal lower triangle at this granularity: every cached position plus staged tiles up to i_hi
+    const int64_t wgs_per_range = (int64_t)c.batch * Gr.n_heads * (G / Gc);
+    const int64_t n_ct = ceil_div(occupied(ctx, Gr, n_past), ZZ_TILE_SLOTS);  // every occupied cached tile is read
+    for (int64_t iq0 = 0; iq0 < n_new; iq0 += QB) {
+      const int64_t iq_last = (iq0 + QB < n_new ? iq0 + QB : n_new) - 1;
+      const int64_t I_lo = n_past + iq0, k_hi = iq_last / ZZ_TILE_SLOTS;
+      // the causal lower triangle at this granularity: every cached position plus staged tiles up to the diagonal
       const int64_t all = ceil_div(n_past, ZZ_TILE_SLOTS) + k_hi + 1;
-      int64_t v = 0;
-      if (!Gr.streaming) {
-        v = n_ct + k_hi + 1;
-      } else {
-        for (int64_t t = 0; t < n_ct; ++t) {  // cached tiles: visited if any slot is a sink or inside some window
-          bool need = false;
-          for (int64_t s = t * ZZ_TILE_SLOTS; s < (t + 1) * ZZ_TILE_SLOTS && s < occ && !need; ++s) {
-            int64_t pos = s;
-            if (s >= S) {
-              const int64_t r = s - S;
-              pos = S + r + W * ((n_past - 1 - S - r) / W);
-            }
-            need = pos < S || pos > i_lo - W;
-          }
-          v += need;
-        }
-        int64_t kk = 0;
+      int64_t ks_end = 0, kw_begin = 0;
+      if (Gr.streaming) {
         if (n_past < S) {
           const int64_t e = (S - 1 - n_past) / ZZ_TILE_SLOTS;
-          kk = (e < k_hi ? e : k_hi) + 1;
-          v += kk;
+          ks_end = (e < k_hi ? e : k_hi) + 1;
         }
-        const int64_t first_win = i_lo - W + 1 - n_past;
-        if (first_win > 0 && first_win / ZZ_TILE_SLOTS > kk) kk = first_win / ZZ_TILE_SLOTS;
-        if (k_hi >= kk) v += k_hi - kk + 1;
+        const int64_t first_win = I_lo - W + 1 - n_past;
+        kw_begin = first_win > 0 ? first_win / ZZ_TILE_SLOTS : 0;
+        if (kw_begin < ks_end) kw_begin = ks_end;
       }
-      vis += v * waves_per_range;
-      cau += all * waves_per_range;
+      const int64_t v = n_ct + ks_end + (k_hi >= kw_begin ? k_hi - kw_begin + 1 : 0);
+      vis += v * wgs_per_range;
+      cau += all * wgs_per_range;
     }
   }
   *visited = vis;

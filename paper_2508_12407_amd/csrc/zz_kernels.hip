@@ -319,16 +319,60 @@ __global__ void zz_zero_kernel(int *p, int n) {
 
 // --------------------------------------------------------------------------
 // Prefill: flash-style over KV tiles, columns = 16 query positions of one head.
-// A wave owns NB column blocks: Gc heads of the group x (NB/Gc) blocks of 16
-// consecutive query positions, so a loaded K/V tile is reused NB times.
+// A workgroup owns 4*QW consecutive query positions of one KV head (all its G
+// query heads, Gc at a time); wave w owns QW = 16*NB/Gc of them as NB column
+// blocks (Gc heads x NB/Gc blocks of 16 positions), so every K/V operand it reads
+// is used by NB MFMAs.  K/V tiles travel HBM/L2 -> LDS once per workgroup with
+// direct-to-LDS loads (global_load_lds_dwordx4: each wave deposits 1 KiB chunks,
+// lane L at byte L*16, i.e. the operand image unchanged), STAGES tiles deep, and
+// each wave reads its operands back with conflict-free ds_read_b128.
+// Keys come from the cached tiles (positions < n_past), then from the staged
+// chunk (position = n_past + index).  Staged tiles no query of the workgroup can
+// see (above the diagonal; for streaming heads also between sink and window) are
+// never loaded.
 // grid (query blocks, heads of the group * head chunks, B), 4 waves.
-// Keys come from the cached tiles (positions < n_past) and then from the staged
-// chunk (position = n_past + index).  Tiles in which no key is visible to any of
-// the wave's queries are skipped without being loaded.
 // --------------------------------------------------------------------------
-template <int D, int NB>
+typedef __attribute__((address_space(3))) void lds_void;
+
+// N consecutive 1 KiB chunks, global -> LDS, without passing through registers: lane L's
+// 16 bytes at src_lane + j*1024 land at LDS byte lds_base + j*1024 + L*16.  Written as
+// asm so that the compiler's wait-count insertion does not tie every later LDS read to
+// these loads (it would wait for all of them, prefetches included); the loop below
+// waits with an explicit vmcnt for exactly the tile it is about to read.
+template <int N>
+__device__ __forceinline__ void dma_to_lds(const uint4 *src_lane, unsigned lds_base) {
+  static_assert(N == 1 || N == 2 || N == 4, "chunks per wave");
+  if constexpr (N == 4)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:1024\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:2048\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:3072" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+  if constexpr (N == 2)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:1024" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+  if constexpr (N == 1)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+}
+
+__device__ __forceinline__ float max_over_kg(float v) {
+  // lanes L, L^16, L^32, L^48 hold the four key groups of one column
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m1 = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
+  const unsigned w = __builtin_bit_cast(unsigned, m1);
+  auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+}
+
+template <int D, int NB, int STAGES>
 __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
   constexpr int KS = D / 32, NL = D / 16, TILE_U4 = 8 * D;
+  constexpr int LPW = 2 * NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a tile each wave brings in
+  __shared__ uint4 s_tiles[STAGES][TILE_U4];
+
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kg = lane >> 4;
   const int G = p.group_size;
@@ -336,15 +380,52 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
   const int hg = blockIdx.y / n_hchunks, hc = blockIdx.y % n_hchunks;
   const int b = blockIdx.z;
   const int g = p.heads[hg];
-  const int QW = 16 * (NB / Gc);  // query positions per wave
-  const int iq0 = (blockIdx.x * ZZ_WAVES_PER_WG + wave) * QW;  // first query index of the wave
-  if (iq0 >= p.n_new) return;  // no barriers below: a wave may leave early
-  const int iq_last = min(iq0 + QW, p.n_new) - 1;
-  const int i_lo = p.n_past + iq0, i_hi = p.n_past + iq_last;
+  const int QW = 16 * (NB / Gc);
+  const int iq_wg = blockIdx.x * ZZ_WAVES_PER_WG * QW;           // first query index of the workgroup
+  const int iq0 = iq_wg + wave * QW;                             // ... of the wave
+  const bool wave_active = iq0 < p.n_new;                        // idle waves still move tiles and meet barriers
+  const int i_lo = p.n_past + iq0;                               // the wave's first query position
+  const int I_lo = p.n_past + iq_wg;                             // the workgroup's range of query positions
+  const int I_hi = p.n_past + min(iq_wg + ZZ_WAVES_PER_WG * QW, p.n_new) - 1;
   const bool streaming = p.grp.streaming != 0;
   const int S = p.sink, W = p.window;
+  const float c = p.scale_log2e;
 
-  // per column block: head, query position, Q operand
+  // ---- the workgroup's tile sequence: cached tiles, then staged tiles ----
+  const int occ = streaming ? min(p.n_past, S + W) : p.n_past;
+  const int n_ct = (occ + 31) >> 5;
+  const int k_hi = (I_hi - p.n_past) >> 5;
+  int ks_end = 0, kw_begin = 0;
+  if (streaming) {
+    if (p.n_past < S) ks_end = min(k_hi, (S - 1 - p.n_past) >> 5) + 1;     // sink tokens arriving with this chunk
+    const int first_win = I_lo - W + 1 - p.n_past;                         // oldest window token, as a chunk index
+    kw_begin = max(ks_end, first_win > 0 ? first_win >> 5 : 0);
+  }
+  const int n_tiles = n_ct + ks_end + max(0, k_hi - kw_begin + 1);
+  const uint4 *ctiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4;
+  const uint4 *stiles = (const uint4 *)p.stage + ((int64_t)b * p.n_kv_heads + g) * p.stage_tiles * TILE_U4;
+
+  // n-th tile of the sequence -> (pointer, cache tile index or -1, staged tile index or -1)
+  auto tile_src = [&](int n, int &ct, int &sk) -> const uint4 * {
+    if (n < n_ct) {
+      ct = n;
+      sk = -1;
+      return ctiles + (int64_t)n * TILE_U4;
+    }
+    const int m = n - n_ct;
+    sk = m < ks_end ? m : kw_begin + (m - ks_end);
+    ct = -1;
+    return stiles + (int64_t)sk * TILE_U4;
+  };
+  auto issue = [&](int n) {
+    int ct, sk;
+    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + lane;   // past the end: a harmless re-read keeps
+    uint4 *dst = &s_tiles[n % STAGES][wave * LPW * 64];                 // the number of loads in flight constant
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)dst);
+    dma_to_lds<LPW>(src + wave * LPW * 64, lds_base);
+  };
+
+  // ---- per column block: head, query position, Q operand ----
   int qpos[NB];
   bf16x8 qop[NB][KS];
 #pragma unroll
@@ -352,141 +433,163 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     const int h = g * G + hc * Gc + cb % Gc;
     const int iq = iq0 + (cb / Gc) * 16 + col;
     const bool ok = iq < p.n_new;
-    qpos[cb] = ok ? p.n_past + iq : -1;  // -1: nothing is visible, output not stored
+    qpos[cb] = ok ? p.n_past + iq : -1;  // -1: sees nothing, output not stored
     const uint4 *qp = (const uint4 *)p.q + (((int64_t)b * p.n_new + (ok ? iq : 0)) * p.n_q_heads + h) * (D / 8) + kg;
 #pragma unroll
     for (int s = 0; s < KS; ++s) qop[cb][s] = as_bf16x8(qp[4 * s]);
   }
+  // Make the Q loads land here.  Otherwise their waits sit at their first use inside the
+  // loop, and since the DMA loads above are invisible to the compiler's counting, those
+  // waits would also drain every K/V prefetch, in every iteration.
+#pragma unroll
+  for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+    for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qop[cb][s]));
+  // the wave's last valid query position (idle waves: none)
+  const int i_hi = p.n_past + min(iq0 + QW, p.n_new) - 1;
 
   f32x4 acc[NB][NL];
-  float m[NB], l[NB];
+  f32x4 lsum[NB];   // row sums of P, produced by an MFMA against an all-ones operand
+  float m[NB];      // running maxima, in raw score units
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb) {
     m[cb] = ZZ_NEG_INF;
-    l[cb] = 0.f;
+    lsum[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < NL; ++i) acc[cb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
-  // One tile: pos[e] is the position of the lane's e-th token (e<4: slot 4kg+e,
-  // e>=4: slot 16+4kg+e-4), or -1 if that slot holds nothing.
-  auto process = [&](const uint4 *src, const int (&pos)[8]) {
-    uint4 kv[2 * NL];
+  // ---- pipeline prologue: STAGES-1 tiles in flight ----
 #pragma unroll
-    for (int i = 0; i < 2 * NL; ++i) kv[i] = src[i * 64];
-    bool any_hole = false;
+  for (int n = 0; n < STAGES - 1; ++n) issue(n);
+
+  for (int n = 0; n < n_tiles; ++n) {
+    // tile n has landed once all but the newest (STAGES-2) tiles' loads of this thread are done
+    if constexpr (STAGES == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (STAGES == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
+    if constexpr (STAGES == 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
+    __syncthreads();          // everyone's chunks of tile n are in; everyone is done with tile n-1
+    issue(n + STAGES - 1);    // into the buffer tile n-1 just vacated
+    if (!wave_active) continue;
+
+    int ct, sk;
+    (void)tile_src(n, ct, sk);
+    const uint4 *tile = &s_tiles[n % STAGES][0] + lane;
+
+    // positions of this lane's 8 keys (e<4: slot 4kg+e, e>=4: slot 16+4kg+e-4); -1 = empty slot
+    int pos[8];
+    bool plain;  // every key of the tile exists and is visible to every query of the wave
+    if (ct >= 0) {
+      const int base = ct * 32;
+      plain = !streaming && base + 32 <= occ;
+      if (!plain) {
+        const int newest = p.n_past - 1 - S;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) any_hole |= pos[e] < 0;
-    if (__any(any_hole)) {
-      unsigned int keep[4];
+        for (int e = 0; e < 8; ++e) {
+          const int slot = base + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
+          int ps = -1;
+          if (slot < occ) ps = (!streaming || slot < S) ? slot : S + (slot - S) + W * ((newest - (slot - S)) / W);
+          pos[e] = ps;
+        }
+      }
+    } else {
+      const int base = sk * 32;
+      plain = !streaming && base + 32 <= p.n_new && p.n_past + base + 31 <= i_lo;
+      if (!plain) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int idx = base + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
+          pos[e] = idx < p.n_new ? p.n_past + idx : -1;
+        }
+      }
+    }
+    // staged tiles wholly above this wave's diagonal (they belong to later waves of the workgroup)
+    if (ct < 0 && p.n_past + sk * 32 > i_hi) continue;
+
+    // ---- scores ----
+    f32x4 s0[NB], s1[NB];
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bf16x8 k0 = as_bf16x8(tile[s * 64]);
+      const bf16x8 k1 = as_bf16x8(tile[(KS + s) * 64]);
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) {
+        s0[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qop[cb][s], s0[cb], 0, 0, 0);
+        s1[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qop[cb][s], s1[cb], 0, 0, 0);
+      }
+    }
+    // ---- online softmax per column block ----
+    bf16x8 P[NB];
+    unsigned keep[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+    if (!plain) {
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         keep[w] = (pos[2 * w] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * w + 1] >= 0 ? 0xffff0000u : 0u);
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        kv[NL + i].x &= keep[0];
-        kv[NL + i].y &= keep[1];
-        kv[NL + i].z &= keep[2];
-        kv[NL + i].w &= keep[3];
-      }
     }
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) {
-      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[s]), qop[cb][s], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[KS + s]), qop[cb][s], s1, 0, 0, 0);
-      }
       float x[8];
-      const int i = qpos[cb];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int j = pos[e];
-        const bool vis = (j >= 0) && (j <= i) && (!streaming || j < S || i - j < W);
-        const float sc = (e < 4 ? s0[e & 3] : s1[e & 3]) * p.scale_log2e;
-        x[e] = vis ? sc : ZZ_NEG_INF;
+      for (int r = 0; r < 4; ++r) {
+        x[r] = s0[cb][r];
+        x[4 + r] = s1[cb][r];
       }
-      float alpha;
-      const bf16x8 P = softmax_step(x, m[cb], l[cb], alpha);
-      if (__any(alpha != 1.0f)) {
+      if (!plain) {
+        const int i = qpos[cb];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int j = pos[e];
+          const bool vis = (j >= 0) && (j <= i) && (!streaming || j < S || i - j < W);
+          x[e] = vis ? x[e] : ZZ_NEG_INF;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mx = max_over_kg(mx);
+      const float m_old = m[cb];
+      const float m_new = fmaxf(m_old, mx);
+      const float m_safe = (m_new == ZZ_NEG_INF) ? 0.f : m_new;
+      const float mc = m_safe * c;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) P[cb][e] = (__bf16)fast_exp2(fmaf(x[e], c, -mc));
+      if (__any(m_new != m_old)) {
+        const float alpha = fast_exp2((m_old - m_safe) * c);
+        lsum[cb] *= alpha;
 #pragma unroll
         for (int k = 0; k < NL; ++k) acc[cb][k] *= alpha;
       }
-#pragma unroll
-      for (int k = 0; k < NL; ++k)
-        acc[cb][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[NL + k]), P, acc[cb][k], 0, 0, 0);
+      m[cb] = m_new;
     }
-  };
-
-  // does any of this lane's tokens matter to any query of the wave?
-  auto lane_needed = [&](const int (&pos)[8]) {
-    bool need = false;
+    // ---- P V, and the row sums of P against the all-ones operand ----
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int j = pos[e];
-      need |= (j >= 0) && (j <= i_hi) && (!streaming || j < S || j > i_lo - W);
-    }
-    return need;
-  };
-
-  // ---- cached tiles ----
-  {
-    const int occ = streaming ? min(p.n_past, S + W) : p.n_past;
-    const int n_ct = (occ + 31) / 32;
-    const uint4 *ctiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4 + lane;
-    const int newest = p.n_past - 1 - S;  // ring offset of the newest cached token
-    for (int t = 0; t < n_ct; ++t) {
-      int pos[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = t * 32 + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
-        int ps = -1;
-        if (slot < occ) {
-          if (!streaming || slot < S)
-            ps = slot;
-          else {
-            const int r = slot - S;
-            ps = S + r + W * ((newest - r) / W);
-          }
-        }
-        pos[e] = ps;
+    for (int k = 0; k < NL; ++k) {
+      uint4 vraw = tile[(NL + k) * 64];
+      if (!plain) {  // empty slots may hold NaN bit patterns
+        vraw.x &= keep[0];
+        vraw.y &= keep[1];
+        vraw.z &= keep[2];
+        vraw.w &= keep[3];
       }
-      if (streaming && !__any(lane_needed(pos))) continue;
-      process(ctiles + (int64_t)t * TILE_U4, pos);
-    }
-  }
-  // ---- staged chunk tiles ----
-  {
-    const uint4 *stiles = (const uint4 *)p.stage + ((int64_t)b * p.n_kv_heads + g) * p.stage_tiles * TILE_U4 + lane;
-    const int k_hi = (i_hi - p.n_past) / 32;
-    auto staged = [&](int k) {
-      int pos[8];
+      const bf16x8 vk = as_bf16x8(vraw);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int idx = k * 32 + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
-        pos[e] = idx < p.n_new ? p.n_past + idx : -1;
-      }
-      process(stiles + (int64_t)k * TILE_U4, pos);
-    };
-    int k = 0;
-    if (streaming) {
-      // sink tokens that arrive with this chunk, then jump to the window
-      const int k_sink_end = (p.n_past < S) ? min(k_hi, (S - 1 - p.n_past) / 32) + 1 : 0;
-      for (; k < k_sink_end; ++k) staged(k);
-      const int first_win = i_lo - W + 1 - p.n_past;  // chunk index of the oldest window token
-      if (first_win > 0) k = max(k, first_win / 32);
+      for (int cb = 0; cb < NB; ++cb)
+        acc[cb][k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vk, P[cb], acc[cb][k], 0, 0, 0);
     }
-    for (; k <= k_hi; ++k) staged(k);
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb)
+      lsum[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P[cb], lsum[cb], 0, 0, 0);
   }
 
   // ---- normalise and store ----
+  if (!wave_active) return;
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb) {
-    float lt = l[cb] + xor_lanes(l[cb], 16);
-    lt += xor_lanes(lt, 32);
     if (qpos[cb] < 0) continue;
-    const float inv = 1.0f / lt;
+    const float inv = 1.0f / lsum[cb][0];   // all 16 rows of the ones-product equal the column's sum
     const int h = g * G + hc * Gc + cb % Gc;
     const int iq = qpos[cb] - p.n_past;
     __bf16 *op = (__bf16 *)p.out + (((int64_t)b * p.n_new + iq) * p.n_q_heads + h) * D + 4 * kg;
@@ -573,6 +676,6 @@ hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {
   const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;  // heads per wave, must divide NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
   const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
-  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, Gc);
-  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, Gc);
+  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB, 3>, grid, dim3(256), s, p, Gc);
+  return launch(zz_prefill_kernel<64, NB, 3>, grid, dim3(256), s, p, Gc);
 }
