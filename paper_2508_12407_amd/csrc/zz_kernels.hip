@@ -319,18 +319,28 @@ __global__ void zz_zero_kernel(int *p, int n) {
 
 // --------------------------------------------------------------------------
 // Prefill: flash-style over KV tiles, columns = 16 query positions of one head.
-// A workgroup owns 4*QW consecutive query positions of one KV head (all its G
-// query heads, Gc at a time); wave w owns QW = 16*NB/Gc of them as NB column
-// blocks (Gc heads x NB/Gc blocks of 16 positions), so every K/V operand it reads
-// is used by NB MFMAs.  K/V tiles travel HBM/L2 -> LDS once per workgroup with
-// direct-to-LDS loads (global_load_lds_dwordx4: each wave deposits 1 KiB chunks,
-// lane L at byte L*16, i.e. the operand image unchanged), STAGES tiles deep, and
-// each wave reads its operands back with conflict-free ds_read_b128.
-// Keys come from the cached tiles (positions < n_past), then from the staged
-// chunk (position = n_past + index).  Staged tiles no query of the workgroup can
-// see (above the diagonal; for streaming heads also between sink and window) are
-// never loaded.
-// grid (query blocks, heads of the group * head chunks, B), 4 waves.
+// A workgroup owns 4*QW consecutive query positions of one KV head; wave w owns
+// QW = 16*NB/Gc of them as NB column blocks (Gc heads x NB/Gc blocks of 16
+// positions), so every K/V operand it reads from LDS feeds NB MFMAs.
+//
+// K/V tiles travel HBM/L2 -> LDS once per workgroup with direct-to-LDS loads
+// (global_load_lds_dwordx4: each wave deposits 1 KiB chunks, lane L at byte L*16,
+// i.e. the operand image unchanged) into two rings of three half-tiles (K parts,
+// V parts); every wave reads operands back with conflict-free ds_read_b128.
+//
+// The loop is software-pipelined over three tiles so that, with one wave per SIMD,
+// the matrix pipe and the vector ALU work at the same time:
+//     iteration n:   S(n+1) = K(n+1) Q^T        (MFMA)
+//                    P(n)   = softmax step on S(n)   (VALU, independent of the above)
+//                    O     += V(n-1)^T P(n-1)   (MFMA)
+// The running reference maximum is only raised when a column's scores exceed it by
+// more than 2^8 (exact in fp32/bf16, P stays <= 256), so the accumulators are
+// rescaled a handful of times per query, not whenever a new maximum appears.
+//
+// Keys come from the cached tiles (positions < n_past), then from the staged chunk
+// (position = n_past + index).  Staged tiles no query of the workgroup can see
+// (above the diagonal; for streaming heads also between sink and window) are never
+// loaded.  grid (query blocks, heads of the group * head chunks, B), 4 waves.
 // --------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -338,16 +348,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 // 16 bytes at src_lane + j*1024 land at LDS byte lds_base + j*1024 + L*16.  Written as
 // asm so that the compiler's wait-count insertion does not tie every later LDS read to
 // these loads (it would wait for all of them, prefetches included); the loop below
-// waits with an explicit vmcnt for exactly the tile it is about to read.
+// waits with an explicit vmcnt for exactly the tiles it is about to read.
 template <int N>
 __device__ __forceinline__ void dma_to_lds(const uint4 *src_lane, unsigned lds_base) {
-  static_assert(N == 1 || N == 2 || N == 4, "chunks per wave");
-  if constexpr (N == 4)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off\n\t"
-                 "global_load_lds_dwordx4 %0, off offset:1024\n\t"
-                 "global_load_lds_dwordx4 %0, off offset:2048\n\t"
-                 "global_load_lds_dwordx4 %0, off offset:3072" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+  static_assert(N == 1 || N == 2, "chunks per wave");
   if constexpr (N == 2)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, off\n\t"
@@ -355,6 +359,11 @@ __device__ __forceinline__ void dma_to_lds(const uint4 *src_lane, unsigned lds_b
   if constexpr (N == 1)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 __device__ __forceinline__ float max_over_kg(float v) {
@@ -367,11 +376,15 @@ __device__ __forceinline__ float max_over_kg(float v) {
   return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
 }
 
-template <int D, int NB, int STAGES>
+#define ZZ_RESCALE_THRESHOLD 8.0f  // in log2 units
+
+template <int D, int NB>
 __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
-  constexpr int KS = D / 32, NL = D / 16, TILE_U4 = 8 * D;
-  constexpr int LPW = 2 * NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a tile each wave brings in
-  __shared__ uint4 s_tiles[STAGES][TILE_U4];
+  constexpr int KS = D / 32, NL = D / 16, HALF_U4 = 4 * D, TILE_U4 = 8 * D;
+  constexpr int CPW = NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a K part (or V part) each wave brings in
+  constexpr int RING = 3;
+  __shared__ uint4 s_k[RING][HALF_U4];
+  __shared__ uint4 s_v[RING][HALF_U4];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kg = lane >> 4;
@@ -381,11 +394,11 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
   const int b = blockIdx.z;
   const int g = p.heads[hg];
   const int QW = 16 * (NB / Gc);
-  const int iq_wg = blockIdx.x * ZZ_WAVES_PER_WG * QW;           // first query index of the workgroup
-  const int iq0 = iq_wg + wave * QW;                             // ... of the wave
-  const bool wave_active = iq0 < p.n_new;                        // idle waves still move tiles and meet barriers
-  const int i_lo = p.n_past + iq0;                               // the wave's first query position
-  const int I_lo = p.n_past + iq_wg;                             // the workgroup's range of query positions
+  const int iq_wg = blockIdx.x * ZZ_WAVES_PER_WG * QW;  // first query index of the workgroup
+  const int iq0 = iq_wg + wave * QW;                    // ... of the wave (may lie past n_new: an idle wave
+                                                        // computes on masked columns and stores nothing)
+  const int i_lo = p.n_past + iq0;                      // the wave's first query position
+  const int I_lo = p.n_past + iq_wg;                    // the workgroup's range of query positions
   const int I_hi = p.n_past + min(iq_wg + ZZ_WAVES_PER_WG * QW, p.n_new) - 1;
   const bool streaming = p.grp.streaming != 0;
   const int S = p.sink, W = p.window;
@@ -397,8 +410,8 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
   const int k_hi = (I_hi - p.n_past) >> 5;
   int ks_end = 0, kw_begin = 0;
   if (streaming) {
-    if (p.n_past < S) ks_end = min(k_hi, (S - 1 - p.n_past) >> 5) + 1;     // sink tokens arriving with this chunk
-    const int first_win = I_lo - W + 1 - p.n_past;                         // oldest window token, as a chunk index
+    if (p.n_past < S) ks_end = min(k_hi, (S - 1 - p.n_past) >> 5) + 1;  // sink tokens arriving with this chunk
+    const int first_win = I_lo - W + 1 - p.n_past;                      // oldest window token, as a chunk index
     kw_begin = max(ks_end, first_win > 0 ? first_win >> 5 : 0);
   }
   const int n_tiles = n_ct + ks_end + max(0, k_hi - kw_begin + 1);
@@ -417,13 +430,22 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     ct = -1;
     return stiles + (int64_t)sk * TILE_U4;
   };
-  auto issue = [&](int n) {
+  // past the end of the sequence a harmless re-read keeps the number of loads in flight constant
+  auto issue_k = [&](int n) {
     int ct, sk;
-    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + lane;   // past the end: a harmless re-read keeps
-    uint4 *dst = &s_tiles[n % STAGES][wave * LPW * 64];                 // the number of loads in flight constant
-    const unsigned lds_base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)dst);
-    dma_to_lds<LPW>(src + wave * LPW * 64, lds_base);
+    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + wave * CPW * 64 + lane;
+    const unsigned dst = (unsigned)(uintptr_t)(lds_void *)&s_k[n % RING][wave * CPW * 64];
+    dma_to_lds<CPW>(src, __builtin_amdgcn_readfirstlane(dst));
   };
+  auto issue_v = [&](int n) {
+    int ct, sk;
+    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + HALF_U4 + wave * CPW * 64 + lane;
+    const unsigned dst = (unsigned)(uintptr_t)(lds_void *)&s_v[n % RING][wave * CPW * 64];
+    dma_to_lds<CPW>(src, __builtin_amdgcn_readfirstlane(dst));
+  };
+
+  issue_k(0);
+  issue_k(1);
 
   // ---- per column block: head, query position, Q operand ----
   int qpos[NB];
@@ -439,21 +461,22 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     for (int s = 0; s < KS; ++s) qop[cb][s] = as_bf16x8(qp[4 * s]);
   }
   // Make the Q loads land here.  Otherwise their waits sit at their first use inside the
-  // loop, and since the DMA loads above are invisible to the compiler's counting, those
-  // waits would also drain every K/V prefetch, in every iteration.
+  // loop, and since the DMA loads are invisible to the compiler's counting, those waits
+  // would also drain every K/V prefetch, in every iteration.
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb)
 #pragma unroll
     for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qop[cb][s]));
-  // the wave's last valid query position (idle waves: none)
-  const int i_hi = p.n_past + min(iq0 + QW, p.n_new) - 1;
 
   f32x4 acc[NB][NL];
-  f32x4 lsum[NB];   // row sums of P, produced by an MFMA against an all-ones operand
-  float m[NB];      // running maxima, in raw score units
+  f32x4 lsum[NB];       // row sums of P, produced by an MFMA against an all-ones operand
+  float mc[NB];         // reference maxima, in log2 units (score * scale * log2 e)
+  float alpha_pend[NB]; // factor the accumulators still have to be multiplied by
+  bool pend = false;
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb) {
-    m[cb] = ZZ_NEG_INF;
+    mc[cb] = ZZ_NEG_INF;
+    alpha_pend[cb] = 1.f;
     lsum[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < NL; ++i) acc[cb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -462,118 +485,111 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
-  // ---- pipeline prologue: STAGES-1 tiles in flight ----
-#pragma unroll
-  for (int n = 0; n < STAGES - 1; ++n) issue(n);
-
-  for (int n = 0; n < n_tiles; ++n) {
-    // tile n has landed once all but the newest (STAGES-2) tiles' loads of this thread are done
-    if constexpr (STAGES == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if constexpr (STAGES == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
-    if constexpr (STAGES == 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
-    __syncthreads();          // everyone's chunks of tile n are in; everyone is done with tile n-1
-    issue(n + STAGES - 1);    // into the buffer tile n-1 just vacated
-    if (!wave_active) continue;
-
-    int ct, sk;
-    (void)tile_src(n, ct, sk);
-    const uint4 *tile = &s_tiles[n % STAGES][0] + lane;
-
-    // positions of this lane's 8 keys (e<4: slot 4kg+e, e>=4: slot 16+4kg+e-4); -1 = empty slot
-    int pos[8];
-    bool plain;  // every key of the tile exists and is visible to every query of the wave
-    if (ct >= 0) {
-      const int base = ct * 32;
-      plain = !streaming && base + 32 <= occ;
-      if (!plain) {
-        const int newest = p.n_past - 1 - S;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int slot = base + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
-          int ps = -1;
-          if (slot < occ) ps = (!streaming || slot < S) ? slot : S + (slot - S) + W * ((newest - (slot - S)) / W);
-          pos[e] = ps;
-        }
-      }
-    } else {
-      const int base = sk * 32;
-      plain = !streaming && base + 32 <= p.n_new && p.n_past + base + 31 <= i_lo;
-      if (!plain) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int idx = base + (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
-          pos[e] = idx < p.n_new ? p.n_past + idx : -1;
-        }
-      }
-    }
-    // staged tiles wholly above this wave's diagonal (they belong to later waves of the workgroup)
-    if (ct < 0 && p.n_past + sk * 32 > i_hi) continue;
-
-    // ---- scores ----
-    f32x4 s0[NB], s1[NB];
+  // ---- the three stages ----
+  auto qk = [&](int n, f32x4(&s0)[NB], f32x4(&s1)[NB]) {
+    const uint4 *kt = &s_k[n % RING][0] + lane;
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const bf16x8 k0 = as_bf16x8(tile[s * 64]);
-      const bf16x8 k1 = as_bf16x8(tile[(KS + s) * 64]);
+      const bf16x8 k0 = as_bf16x8(kt[s * 64]);
+      const bf16x8 k1 = as_bf16x8(kt[(KS + s) * 64]);
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb) {
         s0[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qop[cb][s], s0[cb], 0, 0, 0);
         s1[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qop[cb][s], s1[cb], 0, 0, 0);
       }
     }
-    // ---- online softmax per column block ----
-    bf16x8 P[NB];
-    unsigned keep[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
-    if (!plain) {
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        keep[w] = (pos[2 * w] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * w + 1] >= 0 ? 0xffff0000u : 0u);
+  };
+  // masks of tile n: -inf into the scores of keys a query may not see, and which of the
+  // lane's 8 V tokens exist at all (empty slots may hold NaN bit patterns)
+  auto mask_tile = [&](int n, f32x4(&s0)[NB], f32x4(&s1)[NB], unsigned(&keep)[4]) {
+    int ct, sk;
+    (void)tile_src(n, ct, sk);
+    bool plain;  // every key of the tile exists and is visible to every query of the wave
+    if (ct >= 0)
+      plain = !streaming && ct * 32 + 32 <= occ;
+    else
+      plain = !streaming && sk * 32 + 32 <= p.n_new && p.n_past + sk * 32 + 31 <= i_lo && iq0 + QW <= p.n_new;
+    if (plain) {
+      keep[0] = keep[1] = keep[2] = keep[3] = 0xffffffffu;
+      return;
     }
+    int pos[8];
+    const int newest = p.n_past - 1 - S;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int t = (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
+      int ps = -1;
+      if (ct >= 0) {
+        const int slot = ct * 32 + t;
+        if (slot < occ) ps = (!streaming || slot < S) ? slot : slot + W * ((newest - (slot - S)) / W);
+      } else {
+        const int idx = sk * 32 + t;
+        if (idx < p.n_new) ps = p.n_past + idx;
+      }
+      pos[e] = ps;
+    }
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      keep[w] = (pos[2 * w] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * w + 1] >= 0 ? 0xffff0000u : 0u);
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) {
-      float x[8];
+      const int i = qpos[cb];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        x[r] = s0[cb][r];
-        x[4 + r] = s1[cb][r];
-      }
-      if (!plain) {
-        const int i = qpos[cb];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int j = pos[e];
-          const bool vis = (j >= 0) && (j <= i) && (!streaming || j < S || i - j < W);
-          x[e] = vis ? x[e] : ZZ_NEG_INF;
+      for (int e = 0; e < 8; ++e) {
+        const int j = pos[e];
+        const bool vis = (j >= 0) && (j <= i) && (!streaming || j < S || i - j < W);
+        if (!vis) {
+          if (e < 4)
+            s0[cb][e & 3] = ZZ_NEG_INF;
+          else
+            s1[cb][e & 3] = ZZ_NEG_INF;
         }
       }
-      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mx = max_over_kg(mx);
-      const float m_old = m[cb];
-      const float m_new = fmaxf(m_old, mx);
-      const float m_safe = (m_new == ZZ_NEG_INF) ? 0.f : m_new;
-      const float mc = m_safe * c;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) P[cb][e] = (__bf16)fast_exp2(fmaf(x[e], c, -mc));
-      if (__any(m_new != m_old)) {
-        const float alpha = fast_exp2((m_old - m_safe) * c);
-        lsum[cb] *= alpha;
-#pragma unroll
-        for (int k = 0; k < NL; ++k) acc[cb][k] *= alpha;
-      }
-      m[cb] = m_new;
     }
-    // ---- P V, and the row sums of P against the all-ones operand ----
+  };
+  auto softmax = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB]) {
+    bool grew = false;
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      float mx = fmaxf(fmaxf(fmaxf(s0[cb][0], s0[cb][1]), fmaxf(s0[cb][2], s0[cb][3])),
+                       fmaxf(fmaxf(s1[cb][0], s1[cb][1]), fmaxf(s1[cb][2], s1[cb][3])));
+      const float mxc = max_over_kg(mx) * c;
+      const float old = mc[cb];
+      const bool grow = mxc > old + ZZ_RESCALE_THRESHOLD;  // also true for the first visible key (old = -inf)
+      const float ref = grow ? mxc : old;
+      const float safe = (ref == ZZ_NEG_INF) ? 0.f : ref;  // a column that has seen nothing yet
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        P[cb][r] = (__bf16)fast_exp2(fmaf(s0[cb][r], c, -safe));
+        P[cb][4 + r] = (__bf16)fast_exp2(fmaf(s1[cb][r], c, -safe));
+      }
+      alpha_pend[cb] = grow ? fast_exp2(old - safe) : 1.f;
+      mc[cb] = ref;
+      grew |= grow;
+    }
+    pend = grew;
+  };
+  auto rescale = [&]() {
+    if (__any(pend)) {
+#pragma unroll
+      for (int cb = 0; cb < NB; ++cb) {
+        lsum[cb] *= alpha_pend[cb];
+#pragma unroll
+        for (int k = 0; k < NL; ++k) acc[cb][k] *= alpha_pend[cb];
+      }
+    }
+  };
+  auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned(&keep)[4]) {
+    const uint4 *vt = &s_v[n % RING][0] + lane;
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
-      uint4 vraw = tile[(NL + k) * 64];
-      if (!plain) {  // empty slots may hold NaN bit patterns
-        vraw.x &= keep[0];
-        vraw.y &= keep[1];
-        vraw.z &= keep[2];
-        vraw.w &= keep[3];
-      }
+      uint4 vraw = vt[k * 64];
+      vraw.x &= keep[0];
+      vraw.y &= keep[1];
+      vraw.z &= keep[2];
+      vraw.w &= keep[3];
       const bf16x8 vk = as_bf16x8(vraw);
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb)
@@ -582,14 +598,107 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb)
       lsum[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P[cb], lsum[cb], 0, 0, 0);
+  };
+
+  // The values a stage hands to the next iteration are pinned where they are produced:
+  // being pure register arithmetic, the compiler would otherwise sink the whole softmax
+  // step down to the first use of P, one barrier later, and undo the overlap.
+  auto pin = [&](f32x4(&s0)[NB], f32x4(&s1)[NB], bf16x8(&P)[NB]) {
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) asm volatile("" : "+v"(s0[cb]), "+v"(s1[cb]), "+v"(P[cb]));
+  };
+  // Issue order inside one iteration: matrix and vector instructions alternate (one
+  // 16x16x32 MFMA keeps the matrix pipe busy for four vector-instruction slots), LDS
+  // reads go out ahead of the MFMAs that consume them.
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < 2 * NL; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // two MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // six vector ALU
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+    }
+  };
+
+  // ---- software pipeline ----
+  // Invariant at the barrier of iteration n: K(n+1) and V(n-1) have landed (all loads of
+  // this thread but the 2*CPW newest are done), and every wave has finished iteration n-1,
+  // whose K(n) and V(n-2) slots the loads issued right after the barrier overwrite.
+  f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
+  bf16x8 PA[NB], PB[NB];
+  unsigned keepA[4], keepB[4];
+
+  wait_vmcnt<CPW>();  // K(0)
+  __syncthreads();
+  issue_k(2);
+  issue_v(0);
+  qk(0, sA0, sA1);
+
+  // n = 0: no P V yet
+  wait_vmcnt<2 * CPW>();
+  __syncthreads();
+  issue_k(3);
+  issue_v(1);
+  mask_tile(0, sA0, sA1, keepA);
+  qk(1, sB0, sB1);
+  softmax(sA0, sA1, PA);
+  pin(sB0, sB1, PA);
+
+  int n = 1;
+  for (; n + 1 < n_tiles; n += 2) {
+    // odd n: current scores in B, previous P in A
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    issue_k(n + 3);
+    issue_v(n + 1);
+    rescale();
+    mask_tile(n, sB0, sB1, keepB);
+    qk(n + 1, sA0, sA1);
+    softmax(sB0, sB1, PB);
+    pv(n - 1, PA, keepA);
+    pin(sA0, sA1, PB);
+    // even n+1: current scores in A, previous P in B
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    issue_k(n + 4);
+    issue_v(n + 2);
+    rescale();
+    mask_tile(n + 1, sA0, sA1, keepA);
+    qk(n + 2, sB0, sB1);
+    softmax(sA0, sA1, PA);
+    pv(n, PB, keepB);
+    pin(sB0, sB1, PA);
   }
+  if (n < n_tiles) {  // one odd iteration left
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    issue_k(n + 3);
+    issue_v(n + 1);
+    rescale();
+    mask_tile(n, sB0, sB1, keepB);
+    softmax(sB0, sB1, PB);
+    pv(n - 1, PA, keepA);
+    ++n;
+    // epilogue: last P is in B
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    rescale();
+    pv(n - 1, PB, keepB);
+  } else {
+    // epilogue: last P is in A
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    rescale();
+    pv(n - 1, PA, keepA);
+  }
+  wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
 
   // ---- normalise and store ----
-  if (!wave_active) return;
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb) {
     if (qpos[cb] < 0) continue;
-    const float inv = 1.0f / lsum[cb][0];   // all 16 rows of the ones-product equal the column's sum
+    const float inv = 1.0f / lsum[cb][0];  // all 16 rows of the ones-product equal the column's sum
     const int h = g * G + hc * Gc + cb % Gc;
     const int iq = qpos[cb] - p.n_past;
     __bf16 *op = (__bf16 *)p.out + (((int64_t)b * p.n_new + iq) * p.n_q_heads + h) * D + 4 * kg;
@@ -676,6 +785,6 @@ hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {
   const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;  // heads per wave, must divide NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
   const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
-  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB, 3>, grid, dim3(256), s, p, Gc);
-  return launch(zz_prefill_kernel<64, NB, 3>, grid, dim3(256), s, p, Gc);
+  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, Gc);
+  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, Gc);
 }
