@@ -457,8 +457,8 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
   const Layer &L = ctx->lo.layers[layer];
   const int64_t n_past = L.len, S = c.sink, W = c.window;
   const int G = c.n_q_heads / c.n_kv_heads;
-  const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  const int QB = ZZ_WAVES_PER_WG * 16 * (4 / Gc);  // query positions per workgroup, as zz_launch_prefill chooses them
+  const int Gc = zz_prefill_heads_per_wave(G);
+  const int QB = ZZ_WAVES_PER_WG * 16 * (ZZ_PREFILL_NB / Gc);  // query positions per workgroup, as the launcher chooses
   int64_t vis = 0, cau = 0;
   for (int k = 0; k < 2; ++k) {
     const Group &Gr = L.grp[k];

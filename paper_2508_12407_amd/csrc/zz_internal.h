@@ -12,6 +12,16 @@
 
 #define ZZ_WAVES_PER_WG 4
 
+// Prefill tiling, shared by the launcher and by the host-side tile counter: a wave owns
+// ZZ_PREFILL_NB column blocks of 16 query positions, spread over Gc heads of the KV group.
+#define ZZ_PREFILL_NB 2
+#define ZZ_PREFILL_WG_PER_CU 2
+static inline int zz_prefill_heads_per_wave(int group_size) {
+  int gc = ZZ_PREFILL_NB;
+  while (gc > 1 && group_size % gc != 0) gc >>= 1;
+  return gc;
+}
+
 // One head group of a layer: the heads of one kind (retrieval or streaming).
 struct zz_group_dev {
   char *base;          // arena address of the group's region: [B][n_heads][n_tiles] KV tiles

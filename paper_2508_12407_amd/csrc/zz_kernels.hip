@@ -379,7 +379,7 @@ __device__ __forceinline__ float max_over_kg(float v) {
 #define ZZ_RESCALE_THRESHOLD 8.0f  // in log2 units
 
 template <int D, int NB>
-__global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
+__global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
   constexpr int KS = D / 32, NL = D / 16, HALF_U4 = 4 * D, TILE_U4 = 8 * D;
   constexpr int CPW = NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a K part (or V part) each wave brings in
   constexpr int RING = 3;
@@ -404,7 +404,13 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
   const int S = p.sink, W = p.window;
   const float c = p.scale_log2e;
 
-  // ---- the workgroup's tile sequence: cached tiles, then staged tiles ----
+  // ---- the workgroup's tile sequence ----
+  // Cached tiles come before staged tiles, except that tiles which are "plain" for all
+  // four waves (every slot occupied, every key visible to every query: full cached tiles
+  // of a retrieval head and staged tiles wholly before the workgroup's first query) are
+  // taken first, by the pipelined loop without any mask arithmetic; softmax does not care
+  // about the order of keys.  The rest (ragged last cached tile, diagonal and tail tiles,
+  // everything of a streaming head) goes through the masked loop.
   const int occ = streaming ? min(p.n_past, S + W) : p.n_past;
   const int n_ct = (occ + 31) >> 5;
   const int k_hi = (I_hi - p.n_past) >> 5;
@@ -415,20 +421,33 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     kw_begin = max(ks_end, first_win > 0 ? first_win >> 5 : 0);
   }
   const int n_tiles = n_ct + ks_end + max(0, k_hi - kw_begin + 1);
+  const int nc_full = streaming ? 0 : occ >> 5;        // plain cached tiles
+  const int ns_plain = streaming ? 0 : iq_wg >> 5;     // plain staged tiles (iq_wg is a multiple of 64)
+  int n_fast = nc_full + ns_plain;
+  if (!(n_fast & 1)) n_fast = max(n_fast - 1, 0);      // the pipelined loop takes 1 + 2k tiles
   const uint4 *ctiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4;
   const uint4 *stiles = (const uint4 *)p.stage + ((int64_t)b * p.n_kv_heads + g) * p.stage_tiles * TILE_U4;
 
   // n-th tile of the sequence -> (pointer, cache tile index or -1, staged tile index or -1)
   auto tile_src = [&](int n, int &ct, int &sk) -> const uint4 * {
-    if (n < n_ct) {
+    ct = sk = -1;
+    if (streaming) {
+      if (n < n_ct) {
+        ct = n;
+      } else {
+        const int m = n - n_ct;
+        sk = m < ks_end ? m : kw_begin + (m - ks_end);
+      }
+    } else if (n < nc_full) {
       ct = n;
-      sk = -1;
-      return ctiles + (int64_t)n * TILE_U4;
+    } else if (n < nc_full + ns_plain) {
+      sk = n - nc_full;
+    } else if (n < n_ct + ns_plain) {
+      ct = nc_full;  // the ragged last cached tile
+    } else {
+      sk = n - n_ct;
     }
-    const int m = n - n_ct;
-    sk = m < ks_end ? m : kw_begin + (m - ks_end);
-    ct = -1;
-    return stiles + (int64_t)sk * TILE_U4;
+    return ct >= 0 ? ctiles + (int64_t)ct * TILE_U4 : stiles + (int64_t)sk * TILE_U4;
   };
   // past the end of the sequence a harmless re-read keeps the number of loads in flight constant
   auto issue_k = [&](int n) {
@@ -443,9 +462,6 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     const unsigned dst = (unsigned)(uintptr_t)(lds_void *)&s_v[n % RING][wave * CPW * 64];
     dma_to_lds<CPW>(src, __builtin_amdgcn_readfirstlane(dst));
   };
-
-  issue_k(0);
-  issue_k(1);
 
   // ---- per column block: head, query position, Q operand ----
   int qpos[NB];
@@ -581,15 +597,17 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
       }
     }
   };
-  auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned(&keep)[4]) {
+  auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned *keep) {
     const uint4 *vt = &s_v[n % RING][0] + lane;
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
       uint4 vraw = vt[k * 64];
-      vraw.x &= keep[0];
-      vraw.y &= keep[1];
-      vraw.z &= keep[2];
-      vraw.w &= keep[3];
+      if (keep) {
+        vraw.x &= keep[0];
+        vraw.y &= keep[1];
+        vraw.z &= keep[2];
+        vraw.w &= keep[3];
+      }
       const bf16x8 vk = as_bf16x8(vraw);
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb)
@@ -621,76 +639,89 @@ __global__ __launch_bounds__(256) void zz_prefill_kernel(zz_prefill_params p, in
     }
   };
 
-  // ---- software pipeline ----
+  // ---- software pipeline over the plain tiles [0, n_fast) ----
   // Invariant at the barrier of iteration n: K(n+1) and V(n-1) have landed (all loads of
   // this thread but the 2*CPW newest are done), and every wave has finished iteration n-1,
   // whose K(n) and V(n-2) slots the loads issued right after the barrier overwrite.
-  f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
-  bf16x8 PA[NB], PB[NB];
-  unsigned keepA[4], keepB[4];
-
-  wait_vmcnt<CPW>();  // K(0)
-  __syncthreads();
-  issue_k(2);
-  issue_v(0);
-  qk(0, sA0, sA1);
-
-  // n = 0: no P V yet
-  wait_vmcnt<2 * CPW>();
-  __syncthreads();
-  issue_k(3);
-  issue_v(1);
-  mask_tile(0, sA0, sA1, keepA);
-  qk(1, sB0, sB1);
-  softmax(sA0, sA1, PA);
-  pin(sB0, sB1, PA);
-
-  int n = 1;
-  for (; n + 1 < n_tiles; n += 2) {
-    // odd n: current scores in B, previous P in A
+  // kq / vq: next tile whose K part / V part has not been requested yet.
+  int kq = 0, vq = 0;
+  if (n_fast > 0) {
+    f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
+    bf16x8 PA[NB], PB[NB];
+    issue_k(0);
+    issue_k(1);
+    wait_vmcnt<CPW>();  // K(0)
+    __syncthreads();
+    issue_k(2);
+    issue_v(0);
+    qk(0, sA0, sA1);
+    // n = 0: no P V yet
     wait_vmcnt<2 * CPW>();
     __syncthreads();
-    issue_k(n + 3);
-    issue_v(n + 1);
-    rescale();
-    mask_tile(n, sB0, sB1, keepB);
-    qk(n + 1, sA0, sA1);
-    softmax(sB0, sB1, PB);
-    pv(n - 1, PA, keepA);
-    pin(sA0, sA1, PB);
-    // even n+1: current scores in A, previous P in B
-    wait_vmcnt<2 * CPW>();
-    __syncthreads();
-    issue_k(n + 4);
-    issue_v(n + 2);
-    rescale();
-    mask_tile(n + 1, sA0, sA1, keepA);
-    qk(n + 2, sB0, sB1);
+    issue_k(3);
+    issue_v(1);
+    qk(1, sB0, sB1);
     softmax(sA0, sA1, PA);
-    pv(n, PB, keepB);
     pin(sB0, sB1, PA);
+    for (int n = 1; n < n_fast; n += 2) {
+      // odd n: current scores in B, previous P in A
+      wait_vmcnt<2 * CPW>();
+      __syncthreads();
+      issue_k(n + 3);
+      issue_v(n + 1);
+      rescale();
+      qk(n + 1, sA0, sA1);
+      softmax(sB0, sB1, PB);
+      pv(n - 1, PA, nullptr);
+      pin(sA0, sA1, PB);
+      // even n+1: current scores in A, previous P in B
+      wait_vmcnt<2 * CPW>();
+      __syncthreads();
+      issue_k(n + 4);
+      issue_v(n + 2);
+      rescale();
+      qk(n + 2, sB0, sB1);   // for the last pair this is tile n_fast, which the masked loop redoes
+      softmax(sA0, sA1, PA);
+      pv(n, PB, nullptr);
+      pin(sB0, sB1, PA);
+    }
+    // drain: the last P is in A
+    wait_vmcnt<2 * CPW>();
+    __syncthreads();
+    rescale();
+    pv(n_fast - 1, PA, nullptr);
+    kq = n_fast + 3;
+    vq = n_fast + 1;
   }
-  if (n < n_tiles) {  // one odd iteration left
-    wait_vmcnt<2 * CPW>();
-    __syncthreads();
-    issue_k(n + 3);
-    issue_v(n + 1);
+
+  // ---- masked loop over the remaining tiles, one tile per iteration ----
+  for (int n = n_fast; n < n_tiles; ++n) {
+    if (kq <= n) {  // only when nothing has been requested yet
+      issue_k(n);
+      kq = n + 1;
+    }
+    if (vq <= n) {
+      issue_v(n);
+      vq = n + 1;
+    }
+    wait_vmcnt<0>();
+    __syncthreads();  // tile n is in; everyone is done with tile n-1
+    if (kq <= n + 1 && n + 1 < n_tiles) {
+      issue_k(n + 1);
+      kq = n + 2;
+    }
+    if (vq <= n + 1 && n + 1 < n_tiles) {
+      issue_v(n + 1);
+      vq = n + 2;
+    }
+    f32x4 s0[NB], s1[NB];
+    bf16x8 P[NB];
+    unsigned keep[4];
+    qk(n, s0, s1);
+    mask_tile(n, s0, s1, keep);
+    softmax(s0, s1, P);
     rescale();
-    mask_tile(n, sB0, sB1, keepB);
-    softmax(sB0, sB1, PB);
-    pv(n - 1, PA, keepA);
-    ++n;
-    // epilogue: last P is in B
-    wait_vmcnt<2 * CPW>();
-    __syncthreads();
-    rescale();
-    pv(n - 1, PB, keepB);
-  } else {
-    // epilogue: last P is in A
-    wait_vmcnt<2 * CPW>();
-    __syncthreads();
-    rescale();
-    pv(n - 1, PA, keepA);
+    pv(n, P, keep);
   }
   wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
 
@@ -780,9 +811,9 @@ hipError_t zz_launch_zero(int *p, int n, hipStream_t s) {
 }
 
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {
-  constexpr int NB = 4;
+  constexpr int NB = ZZ_PREFILL_NB;
   const int G = p.group_size;
-  const int Gc = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;  // heads per wave, must divide NB
+  const int Gc = zz_prefill_heads_per_wave(G);  // heads per wave, divides NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
   const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
   if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, Gc);
