@@ -350,15 +350,23 @@ typedef __attribute__((address_space(3))) void lds_void;
 // these loads (it would wait for all of them, prefetches included); the loop below
 // waits with an explicit vmcnt for exactly the tiles it is about to read.
 template <int N>
-__device__ __forceinline__ void dma_to_lds(const uint4 *src_lane, unsigned lds_base) {
+__device__ __forceinline__ void dma_to_lds(const void *tile_base, unsigned lane_byte_off, unsigned lds_base) {
+  // tile_base and lds_base are wave-uniform (scalar registers); only the lane offset is a vector
   static_assert(N == 1 || N == 2, "chunks per wave");
+  // (the builtin returns a signed int: both halves go through unsigned before they are joined)
+  const unsigned long long a = (unsigned long long)tile_base;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
+  const unsigned long long sbase = ((unsigned long long)hi << 32) | (unsigned long long)lo;
   if constexpr (N == 2)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off\n\t"
-                 "global_load_lds_dwordx4 %0, off offset:1024" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %1\n\t"
+                 "global_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(lane_byte_off), "s"(sbase), "s"(lds_base)
+                 : "memory", "m0");
   if constexpr (N == 1)
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %1" ::"v"(lane_byte_off), "s"(sbase), "s"(lds_base)
+                 : "memory", "m0");
 }
 
 template <int N>
@@ -382,7 +390,7 @@ template <int D, int NB>
 __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
   constexpr int KS = D / 32, NL = D / 16, HALF_U4 = 4 * D, TILE_U4 = 8 * D;
   constexpr int CPW = NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a K part (or V part) each wave brings in
-  constexpr int RING = 3;
+  constexpr int RING = 4;  // power of two: the slot of tile n is n & 3
   __shared__ uint4 s_k[RING][HALF_U4];
   __shared__ uint4 s_v[RING][HALF_U4];
 
@@ -449,18 +457,35 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     }
     return ct >= 0 ? ctiles + (int64_t)ct * TILE_U4 : stiles + (int64_t)sk * TILE_U4;
   };
-  // past the end of the sequence a harmless re-read keeps the number of loads in flight constant
+  // Requests for the K part / V part of the n-th tile of the sequence into ring slot n & 3.
+  // Each wave brings CPW KiB-chunks of the part; the tile address stays in scalar registers.
+  const unsigned lane_off = (unsigned)(wave * CPW * 64 + lane) * 16u;
+  const unsigned lds_k0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_k[0][wave * CPW * 64]);
+  const unsigned lds_v0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_v[0][wave * CPW * 64]);
   auto issue_k = [&](int n) {
     int ct, sk;
-    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + wave * CPW * 64 + lane;
-    const unsigned dst = (unsigned)(uintptr_t)(lds_void *)&s_k[n % RING][wave * CPW * 64];
-    dma_to_lds<CPW>(src, __builtin_amdgcn_readfirstlane(dst));
+    const uint4 *src = tile_src(n, ct, sk);
+    dma_to_lds<CPW>(src, lane_off, lds_k0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
   };
   auto issue_v = [&](int n) {
     int ct, sk;
-    const uint4 *src = tile_src(min(n, n_tiles - 1), ct, sk) + HALF_U4 + wave * CPW * 64 + lane;
-    const unsigned dst = (unsigned)(uintptr_t)(lds_void *)&s_v[n % RING][wave * CPW * 64];
-    dma_to_lds<CPW>(src, __builtin_amdgcn_readfirstlane(dst));
+    const uint4 *src = tile_src(n, ct, sk) + HALF_U4;
+    dma_to_lds<CPW>(src, lane_off, lds_v0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
+  };
+  // The same for the pipelined loop, whose tiles are two plain runs (cached, then staged):
+  // branch-free scalar arithmetic.  Past its last tile the loop keeps requesting that tile
+  // again (the loads in flight stay constant; the masked loop requests what it needs itself).
+  auto fast_src = [&](int n) -> const uint4 * {
+    const int m = min(n, n_fast - 1);
+    const uint4 *a = ctiles + (int64_t)m * TILE_U4;
+    const uint4 *b2 = stiles + (int64_t)(m - nc_full) * TILE_U4;
+    return m < nc_full ? a : b2;
+  };
+  auto issue_fast_k = [&](int n) {
+    dma_to_lds<CPW>(fast_src(n), lane_off, lds_k0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
+  };
+  auto issue_fast_v = [&](int n) {
+    dma_to_lds<CPW>(fast_src(n) + HALF_U4, lane_off, lds_v0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
   };
 
   // ---- per column block: head, query position, Q operand ----
@@ -503,7 +528,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
 
   // ---- the three stages ----
   auto qk = [&](int n, f32x4(&s0)[NB], f32x4(&s1)[NB]) {
-    const uint4 *kt = &s_k[n % RING][0] + lane;
+    const uint4 *kt = &s_k[n & (RING - 1)][0] + lane;
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -598,7 +623,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     }
   };
   auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned *keep) {
-    const uint4 *vt = &s_v[n % RING][0] + lane;
+    const uint4 *vt = &s_v[n & (RING - 1)][0] + lane;
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
       uint4 vraw = vt[k * 64];
@@ -648,18 +673,18 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   if (n_fast > 0) {
     f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
     bf16x8 PA[NB], PB[NB];
-    issue_k(0);
-    issue_k(1);
+    issue_fast_k(0);
+    issue_fast_k(1);
     wait_vmcnt<CPW>();  // K(0)
     __syncthreads();
-    issue_k(2);
-    issue_v(0);
+    issue_fast_k(2);
+    issue_fast_v(0);
     qk(0, sA0, sA1);
     // n = 0: no P V yet
     wait_vmcnt<2 * CPW>();
     __syncthreads();
-    issue_k(3);
-    issue_v(1);
+    issue_fast_k(3);
+    issue_fast_v(1);
     qk(1, sB0, sB1);
     softmax(sA0, sA1, PA);
     pin(sB0, sB1, PA);
@@ -667,8 +692,8 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       // odd n: current scores in B, previous P in A
       wait_vmcnt<2 * CPW>();
       __syncthreads();
-      issue_k(n + 3);
-      issue_v(n + 1);
+      issue_fast_k(n + 3);
+      issue_fast_v(n + 1);
       rescale();
       qk(n + 1, sA0, sA1);
       softmax(sB0, sB1, PB);
@@ -677,8 +702,8 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       // even n+1: current scores in A, previous P in B
       wait_vmcnt<2 * CPW>();
       __syncthreads();
-      issue_k(n + 4);
-      issue_v(n + 2);
+      issue_fast_k(n + 4);
+      issue_fast_v(n + 2);
       rescale();
       qk(n + 2, sB0, sB1);   // for the last pair this is tile n_fast, which the masked loop redoes
       softmax(sA0, sA1, PA);
@@ -690,8 +715,8 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     __syncthreads();
     rescale();
     pv(n_fast - 1, PA, nullptr);
-    kq = n_fast + 3;
-    vq = n_fast + 1;
+    wait_vmcnt<0>();  // the surplus requests still write LDS; the masked loop's own come after them
+    kq = vq = n_fast;
   }
 
   // ---- masked loop over the remaining tiles, one tile per iteration ----
