@@ -175,6 +175,9 @@ void plan_decode(const zz_ctx *ctx, int cu, const Group &G, int64_t len, int *n_
   int64_t splits = ctx->tune_splits > 0 ? ctx->tune_splits : ceil_div((int64_t)cu * ctx->tune_wg_per_cu, units);
   if (splits < 1) splits = 1;
   int64_t tps = ceil_div(n_tiles, splits);
+  // A short cache (a streaming head's S+W slots) is latency-bound either way: one workgroup
+  // per unit needs no cross-workgroup merge, which costs more than a few extra tiles per wave.
+  if (n_tiles <= 4 * ZZ_WAVES_PER_WG && ctx->tune_splits <= 0) tps = n_tiles;
   if (tps < ZZ_WAVES_PER_WG && ctx->tune_splits <= 0) tps = ZZ_WAVES_PER_WG;
   if (tps > n_tiles) tps = n_tiles;
   splits = ceil_div(n_tiles, tps);

@@ -294,19 +294,55 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
     s_is_last = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.n_splits - 1);
   __syncthreads();
   if (!s_is_last) return;
+  // Three short phases instead of one thread walking all splits (each device-coherent
+  // load is a full memory round trip): (1) all (max, sum) pairs of the unit into LDS, one
+  // per thread; (2) one wave per column turns them into normalised weights 2^(m_s-M)/L
+  // with lane-parallel reductions; (3) each output element is a weighted sum of its
+  // partials, loads issued eight at a time.  The cross-wave buffer is free by now.
+  float *s_ms = &s_o[0][0][0];                 // [16][ZZ_MAX_SPLITS] maxima, then weights
+  float *s_ls = s_ms + 16 * ZZ_MAX_SPLITS;     // [16][ZZ_MAX_SPLITS] sums
+  static_assert(sizeof(s_o) >= 2 * 16 * ZZ_MAX_SPLITS * sizeof(float), "merge scratch fits the reduction buffer");
+  const int ns = p.n_splits;
+  for (int idx = threadIdx.x; idx < G * ns; idx += 256) {
+    const int c = idx / ns, s = idx - c * ns;
+    const int64_t row = ((int64_t)b * p.n_q_heads + g * G + c) * ZZ_MAX_SPLITS + s;
+    s_ms[c * ZZ_MAX_SPLITS + s] = load_device_coherent(p.part_ml + row * 2);
+    s_ls[c * ZZ_MAX_SPLITS + s] = load_device_coherent(p.part_ml + row * 2 + 1);
+  }
+  __syncthreads();
+  for (int c = wave; c < G; c += ZZ_WAVES_PER_WG) {
+    float m0 = lane < ns ? s_ms[c * ZZ_MAX_SPLITS + lane] : ZZ_NEG_INF;
+    float m1 = lane + 64 < ns ? s_ms[c * ZZ_MAX_SPLITS + lane + 64] : ZZ_NEG_INF;
+    float M = fmaxf(m0, m1);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, xor_lanes(M, o));
+    const float f0 = lane < ns ? fast_exp2(m0 - M) : 0.f;        // every split saw at least one key: M is finite
+    const float f1 = lane + 64 < ns ? fast_exp2(m1 - M) : 0.f;
+    float L = (lane < ns ? s_ls[c * ZZ_MAX_SPLITS + lane] * f0 : 0.f) +
+              (lane + 64 < ns ? s_ls[c * ZZ_MAX_SPLITS + lane + 64] * f1 : 0.f);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) L += xor_lanes(L, o);
+    const float inv = 1.0f / L;
+    if (lane < ns) s_ms[c * ZZ_MAX_SPLITS + lane] = f0 * inv;
+    if (lane + 64 < ns) s_ms[c * ZZ_MAX_SPLITS + lane + 64] = f1 * inv;
+  }
+  __syncthreads();
   for (int idx = threadIdx.x; idx < G * D; idx += 256) {
     const int c = idx / D, d = idx % D;
     const int h = g * G + c;
-    const int64_t row0 = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS;
-    float M = ZZ_NEG_INF;
-    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, load_device_coherent(p.part_ml + (row0 + s) * 2));
-    float L = 0.f, O = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
-      const float f = fast_exp2(load_device_coherent(p.part_ml + (row0 + s) * 2) - M);
-      L += load_device_coherent(p.part_ml + (row0 + s) * 2 + 1) * f;
-      O += load_device_coherent(p.part_o + (row0 + s) * D + d) * f;
+    const float *po = p.part_o + ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS * D + d;
+    const float *wt = s_ms + c * ZZ_MAX_SPLITS;
+    float O = 0.f;
+    int s = 0;
+    for (; s + 8 <= ns; s += 8) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = load_device_coherent(po + (int64_t)(s + j) * D);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) O = fmaf(v[j], wt[s + j], O);
     }
-    ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
+    for (; s < ns; ++s) O = fmaf(load_device_coherent(po + (int64_t)s * D), wt[s], O);
+    ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)O;
   }
   if (threadIdx.x == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
