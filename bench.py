@@ -128,24 +128,31 @@ class DecodeRun:
         self.out = torch.empty_like(self.q)
         torch.cuda.synchronize()
 
-    def step(self, attention_only=False):
+    def step(self, mode="fused"):
+        """One decode step of the whole stack.  fused: zz_decode_step (append inside the
+        attention launch); separate: zz_kv_append then zz_attn_decode; attention: only
+        zz_attn_decode on the cache as it stands."""
         st, ctx = self.st, self.st.ctx
         sp = st.stream_ptr()
         n_pre = self.N - 1
         for l in range(self.w.n_layers):
-            if not attention_only:
+            if mode == "fused":
                 ctx.set_layer_len(l, n_pre)
-                ctx.kv_append(l, self.k1[l], self.v1[l], 1, sp)
-            ctx.attn_decode(l, self.q[l], self.out[l], sp)
+                ctx.decode_step(l, self.q[l], self.k1[l], self.v1[l], self.out[l], sp)
+            else:
+                if mode == "separate":
+                    ctx.set_layer_len(l, n_pre)
+                    ctx.kv_append(l, self.k1[l], self.v1[l], 1, sp)
+                ctx.attn_decode(l, self.q[l], self.out[l], sp)
 
-    def timed(self, steps, warmup, attention_only=False):
+    def timed(self, steps, warmup, mode="fused"):
         torch = self.torch
         for _ in range(warmup):
-            self.step(attention_only)
+            self.step(mode)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            self.step(attention_only)
+            self.step(mode)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
@@ -284,7 +291,8 @@ def bench_decode(args, wname):
         torch.cuda.synchronize()
         del src, dst
     t_step = run.timed(args.steps, args.warmup)
-    t_attn = run.timed(args.steps, args.warmup, attention_only=True)
+    t_sep = run.timed(args.steps, args.warmup, mode="separate")
+    t_attn = run.timed(args.steps, args.warmup, mode="attention")
     t_graph = None if args.no_graph else run.timed_graph(args.steps, args.warmup)
     t_launch = run.time_retrieval_launch(max(3, args.steps // 4))
     nbytes = run.bytes_per_step()
@@ -303,10 +311,12 @@ def bench_decode(args, wname):
         "config": {"workload": wname, "layout": "zigzag", "n_layers": w.n_layers, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "batch": w.batch, "context": w.context,
                    "sink": w.sink, "window": w.window, "streaming_layers": w.n_streaming_layers,
-                   "launch": "plain stream launches, append + attention per layer",
+                   "launch": "plain stream launches, one zz_decode_step (append fused into the attention launch) per layer",
                    "retrieval_split_k": {"splits": ns, "tiles_per_split": tps}},
         "achieved_GBps": nbytes / t_step / 1e9, "algorithmic_bytes_per_step": nbytes,
         "attention_only": {"us_per_token": t_attn / w.batch * 1e6, "GBps": nbytes / t_attn / 1e9},
+        "separate_append": {"us_per_token": t_sep / w.batch * 1e6, "GBps": nbytes / t_sep / 1e9,
+                            "note": "zz_kv_append + zz_attn_decode per layer (two launches)"},
         "roofline": {"bound": "hbm", "kernel": "zz_decode_kernel<128>, one retrieval layer (split-K merge included)",
                      "achieved": per_launch / t_launch / 1e9 if t_launch else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": per_launch / t_launch / 1e9 / HBM_PEAK_GBPS if t_launch else None,
@@ -321,7 +331,7 @@ def bench_decode(args, wname):
         torch.cuda.empty_cache()
         mixed = DecodeRun(w, "mixed", args.seed, args, fill="random")
         tm = mixed.timed(args.steps, args.warmup)
-        tma = mixed.timed(args.steps, args.warmup, attention_only=True)
+        tma = mixed.timed(args.steps, args.warmup, mode="attention")
         out["mixed_head_layout"] = {"us_per_token": tm / w.batch * 1e6, "ms_per_step": tm * 1e3,
                                     "attention_only_us_per_token": tma / w.batch * 1e6,
                                     "GBps": mixed.bytes_per_step() / tm / 1e9,

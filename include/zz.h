@@ -110,6 +110,16 @@ int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, co
  * ZZ_ESTATE if the layer is empty.  Uses the workspace. */
 int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream);
 
+/* One decode step of a layer in a single launch per head kind: appends the newest
+ * token's rows (k_new, v_new: DEVICE [B, 1, Hkv, D]) and attends from it (q, out:
+ * DEVICE [B, Hq, D]).  Same result, same cache contents and same length afterwards as
+ * zz_kv_append(ctx, layer, k_new, v_new, 1, stream) followed by
+ * zz_attn_decode(ctx, layer, q, out, stream); it removes the separate append launch,
+ * the remaining per-layer overhead next to the one attention of Section 2.2.
+ * ZZ_ENOSPC if the layer is full; other errors as for the two calls. */
+int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
+                   void *stream);
+
 /* Tokens appended to the layer so far, or a negative error code. */
 int64_t zz_layer_len(const zz_ctx *ctx, int layer);
 /* Overwrite a layer's length (restoring a snapshot of the arena). 0 <= len <= max_ctx. */

@@ -52,6 +52,7 @@ def _load():
         "zz_kv_append": (I, [V, I, V, V, I, V]),
         "zz_attn_prefill": (I, [V, I, V, V, V, I, V, V]),
         "zz_attn_decode": (I, [V, I, V, V, V]),
+        "zz_decode_step": (I, [V, I, V, V, V, V, V]),
         "zz_layer_len": (I64, [V, I]),
         "zz_set_layer_len": (I, [V, I, I64]),
         "zz_layer_launches": (I, [V, I]),
@@ -152,6 +153,10 @@ class Context:
 
     def attn_decode(self, layer, q, out, stream=None):
         self._chk(lib.zz_attn_decode(self._h, layer, _ptr(q), _ptr(out), stream), "zz_attn_decode")
+
+    def decode_step(self, layer, q, k_new, v_new, out, stream=None):
+        self._chk(lib.zz_decode_step(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream),
+                  "zz_decode_step")
 
     def layer_len(self, layer):
         return int(lib.zz_layer_len(self._h, layer))

@@ -361,14 +361,20 @@ int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, i
   return ZZ_OK;
 }
 
-int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream) {
+// Shared by zz_attn_decode (k_new == nullptr: the newest token is already cached) and
+// zz_decode_step (the newest token is appended by the attention launch itself).
+static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
+                       void *stream) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
-  if (!q || !out) return ZZ_EINVAL;
-  if (misaligned(q, 16) || misaligned(out, 16)) return ZZ_EALIGN;
+  const bool fused = k_new != nullptr || v_new != nullptr;
+  if (!q || !out || (fused && (!k_new || !v_new))) return ZZ_EINVAL;
+  if (misaligned(q, 16) || misaligned(out, 16) || misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
   Layer &L = ctx->lo.layers[layer];
-  if (L.len <= 0) return ZZ_ESTATE;
   const zz_config &c = ctx->cfg;
+  if (fused && L.len + 1 > c.max_ctx) return ZZ_ENOSPC;
+  const int64_t len = L.len + (fused ? 1 : 0);  // tokens the attention sees
+  if (len <= 0) return ZZ_ESTATE;
   const int cu = num_cu(ctx);
   int *counters = (int *)(ctx->ws + ctx->lo.ws_counters);
   if (!ctx->counters_zeroed) {
@@ -388,9 +394,12 @@ int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *strea
     p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
     p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
     p.counters = counters;
-    p.n_valid = (int)occupied(ctx, G, L.len);
+    p.k_new = k_new;
+    p.v_new = v_new;
+    p.new_slot = fused ? (int32_t)slot_rule(G.streaming, len - 1, c.sink, c.window) : -1;
+    p.n_valid = (int)occupied(ctx, G, len);
     p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
-    plan_decode(ctx, cu, G, L.len, &p.n_splits, &p.tiles_per_split);
+    plan_decode(ctx, cu, G, len, &p.n_splits, &p.tiles_per_split);
     p.batch = c.batch;
     p.n_q_heads = c.n_q_heads;
     p.n_kv_heads = c.n_kv_heads;
@@ -399,7 +408,18 @@ int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *strea
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
     if (hipError_t e = zz_launch_decode(p, (hipStream_t)stream)) return hip_failed("decode kernel", e);
   }
+  L.len = len;
   return ZZ_OK;
+}
+
+int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream) {
+  return decode_impl(ctx, layer, q, nullptr, nullptr, out, stream);
+}
+
+int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
+                   void *stream) {
+  if (!k_new || !v_new) return ZZ_EINVAL;
+  return decode_impl(ctx, layer, q, k_new, v_new, out, stream);
 }
 
 int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, int n_new,

@@ -49,6 +49,8 @@ struct zz_decode_params {
   float *part_o;                  // [B, Hq, ZZ_MAX_SPLITS, D]
   float *part_ml;                 // [B, Hq, ZZ_MAX_SPLITS, 2]  (max in log2 units, sum)
   int *counters;                  // [B, Hkv] workgroups of the unit that have finished; 0 between launches
+  const void *k_new, *v_new;      // fused append: [B, 1, Hkv, D] rows of the newest token (or null)
+  int32_t new_slot;               // slot the newest token goes to, -1 if it is already in the cache
   int32_t n_valid;                // occupied slots (prefix of the cache)
   int32_t n_tiles_valid;          // ceil(n_valid / 32)
   int32_t tiles_per_split, n_splits;

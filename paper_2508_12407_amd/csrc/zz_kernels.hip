@@ -48,6 +48,10 @@ __device__ __forceinline__ float load_device_coherent(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ uint4 pick(bool c, uint4 a, uint4 b) {
+  return make_uint4(c ? a.x : b.x, c ? a.y : b.y, c ? a.z : b.z, c ? a.w : b.w);
+}
+
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // --------------------------------------------------------------------------
@@ -168,13 +172,62 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
   for (int i = 0; i < NL; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m = ZZ_NEG_INF, l = 0.f;
 
-  auto load_tile = [&](uint4(&kv)[2 * NL], int t) {
+  auto load_tile = [&](uint4(&kv)[2 * NL], int t) __attribute__((always_inline)) {
     const uint4 *src = tiles + (int64_t)t * TILE_U4;
 #pragma unroll
     for (int i = 0; i < 2 * NL; ++i) kv[i] = load_stream(src + i * 64);
   };
 
-  auto compute = [&](uint4(&kv)[2 * NL], int t) {
+  // ---- fused append (decode step): the newest token's K, V rows ----
+  // Exactly one wave of the grid reads the tile the new token belongs to.  That wave
+  // overwrites, in the registers it has just loaded, the lanes' pieces of the new
+  // token's slot with the new rows, and stores the same pieces to the cache for the
+  // steps to come; nobody else reads that slot in this launch, and what it held (the
+  // token evicted from a ring, or nothing) is replaced in registers whatever the load saw.
+  const int tile_new = p.new_slot >> 5;  // new_slot < 0: nothing to append
+  const bool owner = p.new_slot >= 0 && tile_new >= t0 + wave && tile_new < t1 && ((tile_new - t0 - wave) & 3) == 0;
+  uint4 knew[KS];
+  unsigned short vnew[NL];
+  if (owner) {
+    const uint4 *kp = (const uint4 *)p.k_new + ((int64_t)b * p.n_kv_heads + g) * (D / 8) + kg;
+    const unsigned short *vp = (const unsigned short *)p.v_new + ((int64_t)b * p.n_kv_heads + g) * D + col;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) knew[s] = kp[4 * s];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) vnew[i] = vp[16 * i];
+  }
+  auto patch_new_token = [&](uint4(&kv)[2 * NL]) __attribute__((always_inline)) {
+    const int tn = p.new_slot & 31, jn = tn & 15, kgn = jn >> 2;
+    const int en = 4 * (tn >> 4) + (tn & 3);  // which of the lane's 8 V tokens
+    uint4 *tile = const_cast<uint4 *>(tiles) - lane + (int64_t)tile_new * TILE_U4;
+    // (value selects with constant register indices: a conditional store into kv[] would
+    // turn into an indexed one and push the tile buffers out of registers)
+    const bool in_lo = col == jn && tn < 16, in_hi = col == jn && tn >= 16;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kv[s] = pick(in_lo, knew[s], kv[s]);
+      kv[KS + s] = pick(in_hi, knew[s], kv[KS + s]);
+      if (col == jn) tile[((tn >> 4) * (D / 8) + 4 * s + kg) * 16 + jn] = knew[s];
+    }
+    if (kg == kgn) {
+      unsigned short *vt = (unsigned short *)tile + 32 * D;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        unsigned w[4] = {kv[NL + i].x, kv[NL + i].y, kv[NL + i].z, kv[NL + i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const unsigned lo = (en == 2 * j) ? (unsigned)vnew[i] : (w[j] & 0xffffu);
+          const unsigned hi = (en == 2 * j + 1) ? ((unsigned)vnew[i] << 16) : (w[j] & 0xffff0000u);
+          w[j] = lo | hi;
+        }
+        kv[NL + i] = make_uint4(w[0], w[1], w[2], w[3]);
+        vt[(((i * 4 + kgn) * 16 + col) << 3) + en] = vnew[i];
+      }
+    }
+  };
+
+  auto compute = [&](uint4(&kv)[2 * NL], int t) __attribute__((always_inline)) {
+    if (owner && t == tile_new) patch_new_token(kv);
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {

@@ -56,6 +56,12 @@ class Stack:
         self.ctx.attn_decode(layer, q, out, self.stream_ptr())
         return out
 
+    def decode_step(self, layer, q, k_new, v_new, out=None):
+        if out is None:
+            out = torch.empty_like(q)
+        self.ctx.decode_step(layer, q, k_new, v_new, out, self.stream_ptr())
+        return out
+
     def arena_host(self) -> np.ndarray:
         torch.cuda.synchronize()
         return self.arena.cpu().numpy()

@@ -176,6 +176,12 @@ def test_entry_point_error_paths_launch_nothing():
     assert L.zz_attn_decode(h, 5, A, A, None) == E["ERANGE"]
     assert L.zz_attn_decode(h, 0, None, A, None) == E["EINVAL"]
     assert L.zz_attn_decode(h, 0, A, A + 8, None) == E["EALIGN"]
+    assert L.zz_decode_step(h, 0, A, None, A, A, None) == E["EINVAL"]
+    assert L.zz_decode_step(h, 0, A, A, None, A, None) == E["EINVAL"]
+    assert L.zz_decode_step(h, 0, None, A, A, A, None) == E["EINVAL"]
+    assert L.zz_decode_step(h, 3, A, A, A, A, None) == E["ERANGE"]
+    assert L.zz_decode_step(h, 0, A, A + 6, A, A, None) == E["EALIGN"]
+    assert L.zz_decode_step(None, 0, A, A, A, A, None) == E["EINVAL"]
     assert L.zz_attn_prefill(h, 0, A, A, A, 1025, A, None) == E["ERANGE"]    # > max_chunk
     assert L.zz_attn_prefill(h, 0, A, A, A, -3, A, None) == E["ERANGE"]
     assert L.zz_attn_prefill(h, 0, A, None, A, 4, A, None) == E["EINVAL"]
@@ -185,6 +191,9 @@ def test_entry_point_error_paths_launch_nothing():
     assert L.zz_set_layer_len(h, 0, 1099) == 0 and ctx.layer_len(0) == 1099
     assert L.zz_kv_append(h, 0, A, A, 2, None) == E["ENOSPC"] and ctx.layer_len(0) == 1099
     assert L.zz_attn_prefill(h, 0, A, A, A, 2, A, None) == E["ENOSPC"]
+    assert L.zz_set_layer_len(h, 0, 1100) == 0
+    assert L.zz_decode_step(h, 0, A, A, A, A, None) == E["ENOSPC"] and ctx.layer_len(0) == 1100
+    assert L.zz_set_layer_len(h, 0, 1099) == 0
     assert L.zz_set_layer_len(h, 0, 1101) == E["ERANGE"] and L.zz_set_layer_len(h, 0, -1) == E["ERANGE"]
     assert ctx.layer_len(7) == E["ERANGE"] and ctx.layer_launches(7) == E["ERANGE"]
     assert L.zz_reset(h) == 0 and ctx.layer_len(0) == 0

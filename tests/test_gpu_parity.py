@@ -141,6 +141,61 @@ def test_decode_split_merge_is_race_free_with_far_more_workgroups_than_cus():
     check(outs[128][7], want, "split merge vs oracle")
 
 
+@pytest.mark.parametrize("D,Hq,Hkv", [(64, 4, 2), (128, 32, 8), (128, 4, 4)])
+def test_decode_step_equals_append_then_decode(D, Hq, Hkv):
+    """zz_decode_step (append fused into the attention launch) against the two-call
+    sequence: same outputs bit for bit, same cache bytes, and both match the oracle.
+    Lengths cross a tile start, the sink edge and several ring wraps."""
+    H, zb = _harness()
+    S, W, B = 16, 64, 2
+    T0, steps = 60, 120                       # 60 -> 180 tokens: the ring (64 slots) wraps, tiles start at 64, 96, ...
+    T = T0 + steps
+    q, k, v = zz_inputs.make_qkv(71 + D, B, T, Hq, Hkv, D)
+    qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+    stacks = [H.Stack(2, Hq, Hkv, D, B, T, S, W, layer_is_streaming=[0, 1], poison_arena=True) for _ in range(2)]
+    for st in stacks:
+        for layer in (0, 1):
+            st.append(layer, kd[:, :T0].contiguous(), vd[:, :T0].contiguous())
+    want = {layer: O.attention_layer(q, k, v, bool(layer), S, W, rows=range(T0, T)) for layer in (0, 1)}
+    for t in range(T0, T):
+        kt, vt, qt = kd[:, t:t + 1].contiguous(), vd[:, t:t + 1].contiguous(), qd[:, t].contiguous()
+        for layer in (0, 1):
+            fused = H.from_dev(stacks[0].decode_step(layer, qt, kt, vt))
+            stacks[1].append(layer, kt, vt)
+            two = H.from_dev(stacks[1].decode(layer, qt))
+            assert np.array_equal(fused, two), (layer, t)
+            check(fused, want[layer][:, t - T0], ("decode_step", layer, t))
+            assert stacks[0].ctx.layer_len(layer) == t + 1
+        if t in (T0, 63, 64, 79, 80, 81, 143, 144, T - 1):
+            a0, a1 = stacks[0].arena_host(), stacks[1].arena_host()
+            for layer, streaming in ((0, False), (1, True)):
+                cap = O.cache_capacity(streaming, S, W, T)
+                slots = np.arange(O.n_occupied(t + 1, streaming, S, W))
+                for which, X in ((0, k), (1, v)):
+                    img, valid = O.expected_cache(zz_inputs.bf16_bits(X), t + 1, streaming, S, W, cap)
+                    for bb in range(B):
+                        for g in range(Hkv):
+                            got = stacks[0].read_cache_rows(a0, layer, which, bb, g, slots)
+                            assert np.array_equal(got, img[bb, g, slots]), (layer, which, t, bb, g)
+                            assert np.array_equal(got, stacks[1].read_cache_rows(a1, layer, which, bb, g, slots))
+
+
+def test_decode_step_from_empty_cache_and_with_many_splits():
+    H, zb = _harness()
+    B, Hq, Hkv, D, S, W, T = 1, 8, 2, 128, 4, 8, 700
+    q, k, v = zz_inputs.make_qkv(81, B, T, Hq, Hkv, D)
+    qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+    st = H.Stack(2, Hq, Hkv, D, B, T, S, W, layer_is_streaming=[0, 1], poison_arena=True)
+    st.ctx.tune(zb.TUNE_DECODE_SPLITS, 5)
+    for layer in (0, 1):
+        want = O.attention_layer(q, k, v, bool(layer), S, W)
+        for t in range(T):                      # every token enters through the fused step, the first into an empty layer
+            got = H.from_dev(st.decode_step(layer, qd[:, t].contiguous(), kd[:, t:t + 1].contiguous(),
+                                            vd[:, t:t + 1].contiguous()))
+            if t < 40 or t % 31 == 0 or t == T - 1:
+                check(got, want[:, t], ("decode_step from empty", layer, t))
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 2), (32, 2), (6, 2)])
 def test_decode_group_sizes(Hq, Hkv):
     # G = 1 (MHA), 8, 16 (the widest column block) and a non-power-of-two group
