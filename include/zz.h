@@ -170,6 +170,21 @@ int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *
  * fraction that the sink + window mask of streaming heads allows (Section 3.3). */
 int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *visited, int64_t *causal);
 
+/* Transport optimisation (Section 2.2, Eq. 5), host only: from converged head importances
+ * alpha (HOST, [n_layers*n_heads], each in [0,1]) choose the p = sparsity*n_layers
+ * layers that become all-streaming.  Heads are first classified as the paper's starting
+ * point does (the p*H heads of smallest alpha are streaming heads); turning a
+ * retrieval head into a streaming one costs +alpha, the reverse costs -omega*alpha, keeping a
+ * head costs 0; the set of p layers minimising the summed cost is returned in
+ * layer_is_streaming (HOST, [n_layers], 0/1; ties go to the lower layer index) and the
+ * minimum in *loss (may be NULL).  The cost of a candidate differs from a constant only by
+ * the sum over its layers of (alpha of the layer's retrieval heads + omega * alpha of its
+ * streaming heads), so sorting the layers by that key gives the same optimum as examining
+ * all C(L,p) candidates one by one, in O(L*H + L log L).  0 <= omega <= 1; 0 <= sparsity <= 1
+ * and sparsity*n_layers must be a whole number (p/L = s), else ZZ_ERANGE. */
+int zz_transport_select(const float *alpha, int n_layers, int n_heads, float sparsity, float omega,
+                        uint8_t *layer_is_streaming, double *loss);
+
 const char *zz_strerror(int code);
 /* What the HIP runtime reported for the calling thread's most recent ZZ_EHIP
  * (which kernel, hipGetErrorString text); "" if there was none. */

@@ -61,6 +61,7 @@ def _load():
         "zz_tune": (I, [V, I, I]),
         "zz_decode_plan": (I, [V, I, I, P(I), P(I)]),
         "zz_prefill_tile_counts": (I, [V, I, I, P(I64), P(I64)]),
+        "zz_transport_select": (I, [P(C.c_float), I, I, C.c_float, C.c_float, P(C.c_uint8), P(C.c_double)]),
         "zz_strerror": (C.c_char_p, [I]),
         "zz_last_error_detail": (C.c_char_p, []),
     }
@@ -104,6 +105,19 @@ def workspace_bytes(cfg):
 
 def slot_of(cfg, layer, kv_head, pos):
     return int(lib.zz_slot_of(C.byref(cfg), layer, kv_head, pos))
+
+
+def transport_select(alpha, sparsity, omega):
+    """Section 2.2, Eq. 5 on the host: alpha [L,H] float32 -> (uint8[L] layer mask, loss)."""
+    a = np.ascontiguousarray(np.asarray(alpha, dtype=np.float32))
+    L, H = a.shape
+    mask = np.zeros(L, dtype=np.uint8)
+    loss = C.c_double()
+    rc = lib.zz_transport_select(a.ctypes.data_as(C.POINTER(C.c_float)), L, H, sparsity, omega,
+                                 mask.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(loss))
+    if rc != 0:
+        raise ZzError(rc, "zz_transport_select")
+    return mask, loss.value
 
 
 def _ptr(t):

@@ -8,7 +8,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libzz.so")
-SOURCES = [os.path.join(CSRC, "zz_api.cpp"), os.path.join(CSRC, "zz_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "zz_api.cpp"), os.path.join(CSRC, "zz_transport.cpp"), os.path.join(CSRC, "zz_kernels.hip")]
 
 
 def hipcc() -> str:
