@@ -5,7 +5,7 @@ A step is one pass of the whole hot path over one batch: for every layer, append
 the new token's K/V (ring evict in streaming layers) and run that layer's single
 attention launch.  Prints ONE JSON line (see the design doc for every field).
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|sweep]
 """
 from __future__ import annotations
 
@@ -353,7 +353,10 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     wname = ALIASES.get(args.workload, args.workload)
-    if wname == "c4_prefill_64k":
+    if wname == "sweep":
+        from bench_sweep import bench_sweep
+        out = bench_sweep(args)
+    elif wname == "c4_prefill_64k":
         from bench_prefill import bench_prefill
         out = bench_prefill(args, wname)
     else:
