@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="do not also time a HIP-graph replay of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 byte counters by)")
+    ap.add_argument("--no-32k", action="store_true",
+                    help="with the default workload: skip the short extra measurement at 32k context, batch 1")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0)
     return ap.parse_args()
@@ -342,6 +344,22 @@ def bench_decode(args, wname):
     return out
 
 
+def short_decode_point(args, wname):
+    """The metric's other context length, measured briefly beside the main workload."""
+    import torch
+    import zz_inputs
+    w = zz_inputs.WORKLOADS[wname]
+    out = {"workload": wname, "batch": w.batch, "context": w.context}
+    for layout in ("zigzag", "mixed"):
+        run = DecodeRun(w, layout, args.seed, args, fill="random")
+        t = run.timed(args.steps, args.warmup)
+        out[layout] = {"us_per_token": t / w.batch * 1e6, "GBps": run.bytes_per_step() / t / 1e9}
+        del run
+        torch.cuda.empty_cache()
+    out["zigzag_speedup"] = out["mixed"]["us_per_token"] / out["zigzag"]["us_per_token"]
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -352,6 +370,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if not os.path.exists(os.path.join(ROOT, "paper_2508_12407_amd", "libzz.so")):
+        import __graft_entry__
+        __graft_entry__.build()       # only when nothing is built; otherwise the library is used as it is
     wname = ALIASES.get(args.workload, args.workload)
     if wname == "sweep":
         from bench_sweep import bench_sweep
@@ -361,6 +382,8 @@ def main():
         out = bench_prefill(args, wname)
     else:
         out = bench_decode(args, wname)
+        if wname == "c3_llama8b_128k_b4" and not args.no_32k:
+            out["at_32k_batch1"] = short_decode_point(args, "c2_llama8b_32k_b1")
     print(json.dumps(out))
 
 
