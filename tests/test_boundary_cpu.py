@@ -268,3 +268,10 @@ def test_prefill_tile_counts_cover_every_needed_tile_and_skip_the_rest(n_past, n
     assert zb.lib.zz_prefill_tile_counts(h, 0, 0, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
     assert zb.lib.zz_prefill_tile_counts(h, 0, 8, None, ctypes.byref(b_)) == E["EINVAL"]
     assert zb.lib.zz_prefill_tile_counts(h, 5, 8, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -410,3 +410,50 @@ def test_prefill_full_size_last_chunk_of_64k_sampled_rows():
             for h in heads:
                 want = O.attention_row(qh[r, h], kh[J, h // G], vh[J, h // G], scale)
                 check(got[r, h], want, ("64k prefill", layer, r, h))
+
+
+def test_decode_step_captured_in_a_hip_graph_replays_identically():
+    """A whole-stack decode step (one zz_decode_step per layer) captured into a HIP graph:
+    every replay, with eager launches and synchronisations in between, must reproduce the
+    eager result (the library records kernels only: no memset nodes, no allocations)."""
+    H, zb = _harness()
+    L, B, Hq, Hkv, D, S, W, T = 4, 2, 8, 2, 128, 16, 64, 900
+    st = H.Stack(L, Hq, Hkv, D, B, T + 4, S, W, layer_is_streaming=[0, 1, 1, 0], poison_arena=True)
+    q, k, v = zz_inputs.make_qkv(91, B, T + 1, Hq, Hkv, D)
+    qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+    for l in range(L):
+        st.append(l, kd[:, :T].contiguous(), vd[:, :T].contiguous())
+    qs = torch.stack([qd[:, T].contiguous() for _ in range(L)])
+    k1, v1 = kd[:, T:T + 1].contiguous(), vd[:, T:T + 1].contiguous()
+    out = torch.zeros_like(qs)
+
+    def step():
+        for l in range(L):
+            st.ctx.set_layer_len(l, T)
+            st.ctx.decode_step(l, qs[l], k1, v1, out[l], st.stream_ptr())
+
+    step()                                   # eager (also clears the split counters outside any capture)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    want0 = O.decode_row(q[:, T], k, v, T, kinds_of(False, Hkv), S, W)
+    want1 = O.decode_row(q[:, T], k, v, T, kinds_of(True, Hkv), S, W)
+    check(H.from_dev(eager[0]), want0, "eager retrieval layer")
+    check(H.from_dev(eager[1]), want1, "eager streaming layer")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        out.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()     # the program's own eager work in between
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        step()                                                          # an eager step between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
