@@ -440,7 +440,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 // waits with an explicit vmcnt for exactly the tiles it is about to read.
 template <int N>
 __device__ __forceinline__ void dma_to_lds(const void *tile_base, unsigned lane_byte_off, unsigned lds_base) {
-  // tile_base and lds_base are wave-uniform (scalar registers); only the lane offset is a vector
+  // tile_base and lds_base are wave-uniform (scalar registers); only the lane offset is a vector.
+  // The compiler does not look inside an asm statement when it inserts wait states: the
+  // s_nop 4 covers both a scalar register written by v_readfirstlane just before (five wait
+  // states before a memory instruction may read it) and the write of M0 (one).
   static_assert(N == 1 || N == 2, "chunks per wave");
   // (the builtin returns a signed int: both halves go through unsigned before they are joined)
   const unsigned long long a = (unsigned long long)tile_base;
@@ -448,12 +451,12 @@ __device__ __forceinline__ void dma_to_lds(const void *tile_base, unsigned lane_
   const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
   const unsigned long long sbase = ((unsigned long long)hi << 32) | (unsigned long long)lo;
   if constexpr (N == 2)
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\t"
                  "global_load_lds_dwordx4 %0, %1\n\t"
                  "global_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(lane_byte_off), "s"(sbase), "s"(lds_base)
                  : "memory", "m0");
   if constexpr (N == 1)
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\t"
                  "global_load_lds_dwordx4 %0, %1" ::"v"(lane_byte_off), "s"(sbase), "s"(lds_base)
                  : "memory", "m0");
 }
