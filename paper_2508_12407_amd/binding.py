@@ -144,7 +144,7 @@ class Context:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:   # (module globals may be gone at interpreter exit)
             lib.zz_destroy(self._h)
             self._h = None
 

@@ -356,6 +356,7 @@ int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, i
   p.head_dim = c.head_dim;
   p.sink = c.sink;
   p.window = c.window;
+  p.only_group = -1;
   if (hipError_t e = zz_launch_append(p, (hipStream_t)stream)) return hip_failed("append kernel", e);
   L.len += n_new;
   return ZZ_OK;

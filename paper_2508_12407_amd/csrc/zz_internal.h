@@ -39,6 +39,7 @@ struct zz_append_params {
   int64_t len;                    // tokens already in the layer
   int32_t n_new, batch, n_kv_heads, head_dim;
   int32_t sink, window;
+  int32_t only_group;             // -1: every head; 0/1: only the heads of that group (the rest belongs to another launch)
 };
 
 struct zz_decode_params {

@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
   const int idx = (int)(tid % p.n_new);
   const int b = (int)(tid / p.n_new);
 
+  if (p.only_group >= 0 && p.head_group[g] != p.only_group) return;
   const zz_group_dev &G = p.grp[p.head_group[g]];
   const int64_t pos = p.len + idx;
   int64_t slot = pos;
@@ -99,6 +100,58 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
     const int d = 8 * c + i;
     const unsigned short val = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xffffu));
     vt[((((d >> 4) * 4 + kgv) * 16 + (d & 15)) << 3) + e] = val;
+  }
+}
+
+// Bulk append into never-evicting heads (retrieval caches, the prefill staging area): one
+// workgroup per (tile, head, sequence).  K rows go out as 16-byte pieces as above; the V rows
+// of the tile are transposed through LDS so that a full tile is written as 16-byte pieces
+// too (the per-token kernel scatters V in 2-byte pieces, which more than doubles the bytes
+// HBM has to write).  A tile only partly covered by the call keeps the 2-byte stores, so
+// slots that already hold older tokens are not touched.
+// grid (tiles touched, heads of group 0, B).
+template <int D>
+__global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p, int first_tile) {
+  constexpr int CH = D / 8;
+  __shared__ unsigned short sv[32][D + 2];
+  const zz_group_dev &G = p.grp[0];
+  const int hi = blockIdx.y, b = blockIdx.z;
+  int g = 0;
+  for (int j = 0; j < p.n_kv_heads; ++j)
+    if (p.head_group[j] == 0 && p.head_index[j] == hi) g = j;
+  const int64_t tile = (int64_t)first_tile + blockIdx.x;
+  const int64_t s_lo = max(tile * 32, p.len), s_hi = min(tile * 32 + 32, p.len + (int64_t)p.n_new);  // slots == positions
+  char *tb = G.base + (((int64_t)b * G.n_heads + hi) * G.n_tiles + tile) * (int64_t)(128 * D);
+  for (int idx = threadIdx.x; idx < 32 * CH; idx += 256) {
+    const int t = idx / CH, c = idx % CH;
+    const int64_t slot = tile * 32 + t;
+    if (slot < s_lo || slot >= s_hi) continue;
+    const int64_t src = ((((int64_t)b * p.n_new + (slot - p.len)) * p.n_kv_heads + g) * D) / 8 + c;
+    ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = ((const uint4 *)p.k_new)[src];
+    const uint4 vv = ((const uint4 *)p.v_new)[src];
+    const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sv[t][8 * c + i] = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xffffu));
+  }
+  __syncthreads();
+  const bool full = s_lo == tile * 32 && s_hi == tile * 32 + 32;
+  unsigned short *vt = (unsigned short *)tb + 32 * D;
+  for (int o = threadIdx.x; o < 4 * D; o += 256) {   // o = (d/16 * 4 + key group) * 16 + d%16: one 16-byte piece of the V image
+    const int dd = o & 15, kgv = (o >> 4) & 3, nb = o >> 6;
+    const int d = 16 * nb + dd;
+    unsigned short e8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) e8[e] = sv[(e < 4 ? 0 : 16) + 4 * kgv + (e & 3)][d];
+    if (full) {
+      ((uint4 *)vt)[o] = make_uint4(e8[0] | ((unsigned)e8[1] << 16), e8[2] | ((unsigned)e8[3] << 16),
+                                    e8[4] | ((unsigned)e8[5] << 16), e8[6] | ((unsigned)e8[7] << 16));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int64_t slot = tile * 32 + (e < 4 ? 0 : 16) + 4 * kgv + (e & 3);
+        if (slot >= s_lo && slot < s_hi) vt[(o << 3) + e] = e8[e];
+      }
+    }
   }
 }
 
@@ -886,7 +939,19 @@ int zz_query_num_cu() {
   return n;
 }
 
-hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s) {
+hipError_t zz_launch_append(const zz_append_params &p0, hipStream_t s) {
+  zz_append_params p = p0;
+  // many tokens into never-evicting heads: the tile-wise kernel; streaming heads (at most S+W
+  // surviving tokens) and short appends: the per-token kernel
+  if (p.n_new >= ZZ_TILE_SLOTS && p.grp[0].n_heads > 0 && p.only_group < 0) {
+    const int first_tile = (int)(p.len / ZZ_TILE_SLOTS);
+    const int last_tile = (int)((p.len + p.n_new - 1) / ZZ_TILE_SLOTS);
+    const dim3 grid(last_tile - first_tile + 1, p.grp[0].n_heads, p.batch);
+    hipError_t e = p.head_dim == 128 ? launch(zz_append_bulk_kernel<128>, grid, dim3(256), s, p, first_tile)
+                                     : launch(zz_append_bulk_kernel<64>, grid, dim3(256), s, p, first_tile);
+    if (e != hipSuccess || p.grp[1].n_heads == 0) return e;
+    p.only_group = 1;
+  }
   const int64_t total = (int64_t)p.batch * p.n_new * p.n_kv_heads * (p.head_dim / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (p.head_dim == 128) return launch(zz_append_kernel<128>, dim3(blocks), dim3(256), s, p);
@@ -913,6 +978,7 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
   p.head_dim = sp.head_dim;
   p.sink = 0;
   p.window = 1;
+  p.only_group = -1;
   return zz_launch_append(p, s);
 }
 
