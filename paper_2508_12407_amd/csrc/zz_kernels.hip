@@ -810,10 +810,10 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   };
 
   // ---- software pipeline over the plain tiles [0, n_fast) ----
-  // Invariant at the barrier of iteration n: K(n+1) and V(n-1) have landed (all loads of
-  // this thread but the 2*CPW newest are done), and every wave has finished iteration n-1,
-  // whose K(n) and V(n-2) slots the loads issued right after the barrier overwrite.
-  // kq / vq: next tile whose K part / V part has not been requested yet.
+  // Iteration n computes scores of tile n+1, softmax of tile n, P V of tile n-1; the loop body
+  // is two iterations (registers alternate between the A and B sets) behind one barrier.
+  // Ring slot of tile t is t & 3, for K parts and V parts alike.
+  // kq / vq (masked loop): next tile whose K part / V part has not been requested yet.
   int kq = 0, vq = 0;
   if (n_fast > 0) {
     f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
@@ -834,21 +834,22 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     softmax(sA0, sA1, PA);
     pin(sB0, sB1, PA);
     for (int n = 1; n < n_fast; n += 2) {
-      // odd n: current scores in B, previous P in A
-      wait_vmcnt<2 * CPW>();
+      // One barrier per two tiles.  At this point K(n+1), K(n+2), V(n-1), V(n) have landed
+      // (everything requested one pair ago) and every wave is done with the previous pair,
+      // whose four ring slots the requests below refill.
+      wait_vmcnt<0>();
       __syncthreads();
       issue_fast_k(n + 3);
       issue_fast_v(n + 1);
+      issue_fast_k(n + 4);
+      issue_fast_v(n + 2);
+      // odd n: current scores in B, previous P in A
       rescale();
       qk(n + 1, sA0, sA1);
       softmax(sB0, sB1, PB);
       pv(n - 1, PA, nullptr);
       pin(sA0, sA1, PB);
       // even n+1: current scores in A, previous P in B
-      wait_vmcnt<2 * CPW>();
-      __syncthreads();
-      issue_fast_k(n + 4);
-      issue_fast_v(n + 2);
       rescale();
       qk(n + 2, sB0, sB1);   // for the last pair this is tile n_fast, which the masked loop redoes
       softmax(sA0, sA1, PA);
@@ -856,7 +857,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       pin(sB0, sB1, PA);
     }
     // drain: the last P is in A
-    wait_vmcnt<2 * CPW>();
+    wait_vmcnt<0>();
     __syncthreads();
     rescale();
     pv(n_fast - 1, PA, nullptr);
