@@ -457,3 +457,42 @@ def test_decode_step_captured_in_a_hip_graph_replays_identically():
         step()                                                          # an eager step between replays
         torch.cuda.synchronize()
         assert torch.equal(out, eager), rep
+
+
+def test_uniform_keys_give_the_mean_over_exactly_the_attended_set_on_gpu():
+    """Closed form on the GPU path itself (no oracle involved): with K = 0 every visible key
+    gets the same weight, so the output is the mean of V over the attended set.  V encodes
+    the key's position in bf16-exact integers, so the means tell which positions were used:
+    streaming: {0..S-1} U {i-W+1..i}; retrieval: {0..i}.  Decode at 32k, prefill rows beside it."""
+    H, zb = _harness()
+    S, W, B, Hq, Hkv, D, T = 64, 256, 1, 8, 2, 128, 32768
+    k = np.zeros((B, T, Hkv, D), np.float32)
+    v = np.zeros((B, T, Hkv, D), np.float32)
+    j = np.arange(T)
+    v[0, :, :, 0] = 1.0
+    v[0, :, :, 1] = (j % 256)[:, None]
+    v[0, :, :, 2] = (j // 256)[:, None]
+    q = zz_inputs.make_qkv(3, B, T, Hq, Hkv, D)[0]
+    C = 512
+    st = H.Stack(2, Hq, Hkv, D, B, T, S, W, max_chunk=C, layer_is_streaming=[0, 1], poison_arena=True)
+    kd, vd, qd = H.to_dev_bf16(k), H.to_dev_bf16(v), H.to_dev_bf16(q)
+    n_past = T - C
+    for layer in (0, 1):
+        st.append(layer, kd[:, :n_past].contiguous(), vd[:, :n_past].contiguous())
+
+    def expect(i, streaming):
+        A = np.concatenate([np.arange(min(S, i + 1)), np.arange(max(S, i - W + 1), i + 1)]) if streaming else np.arange(i + 1)
+        return np.array([1.0, (A % 256).mean(), (A // 256).mean()])
+
+    for layer, streaming in ((0, False), (1, True)):
+        pre = H.from_dev(st.prefill(layer, qd[:, n_past:].contiguous(), kd[:, n_past:].contiguous(),
+                                    vd[:, n_past:].contiguous()))
+        for r in (0, 1, 31, 32, 255, 256, 300, C - 1):
+            want = expect(n_past + r, streaming)
+            for h in (0, Hq - 1):
+                assert np.allclose(pre[0, r, h, :3], want, rtol=2 ** -7, atol=1e-6), (layer, r, h, pre[0, r, h, :3], want)
+        st.append(layer, kd[:, n_past:].contiguous(), vd[:, n_past:].contiguous())
+        dec = H.from_dev(st.decode(layer, qd[:, T - 1].contiguous()))
+        want = expect(T - 1, streaming)
+        assert np.allclose(dec[0, :, :3], want[None, :], rtol=2 ** -7, atol=1e-6), (layer, dec[0, 0, :3], want)
+        assert np.abs(dec[0, :, 3:]).max() == 0.0
