@@ -3,7 +3,15 @@
 
 A step is one pass of the whole hot path over one batch: for every layer, append
 the new token's K/V (ring evict in streaming layers) and run that layer's single
-attention launch.  Prints ONE JSON line (see the design doc for every field).
+attention launch.  Prints ONE JSON line:
+  value            us per generated token = step time / batch, inputs resident in HBM
+  achieved_GBps    algorithmic K+V bytes of the step / step time
+  roofline         the retrieval-layer attention launch alone (HIP events) against the HBM peak
+  cpu_baseline     the fp64 oracle on a sample of the same workload, host threads stated
+  parity_sample    the GPU output of that sample against the oracle
+  mixed_head_layout, at_32k_batch1, separate_append, attention_only, hip_graph_replay: the
+                   same step in the comparison layout / at the other context length / with
+                   the append as its own launch / without the append / replayed from a HIP graph
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|sweep]
 """
@@ -202,6 +210,24 @@ class DecodeRun:
         ms = [a.elapsed_time(b) for a, b in evs]
         return float(np.mean(ms)) * 1e-3
 
+    def read_ceiling(self, nbytes=1 << 31, reps=5):
+        """GB/s of a pure streaming read of the arena with the decode kernel's access pattern
+        (default-policy and non-temporal loads): the practical ceiling beside the 8 TB/s peak."""
+        torch = self.torch
+        nbytes = min(nbytes, self.st.arena_nbytes)
+        out = {}
+        for name, nt in (("default_loads", 0), ("nontemporal_loads", 1)):
+            sp = self.st.stream_ptr()
+            self.st.ctx.probe_read(self.st.arena, nbytes, nt, sp)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                self.st.ctx.probe_read(self.st.arena, nbytes, nt, sp)
+            e1.record()
+            torch.cuda.synchronize()
+            out[name] = nbytes / (e0.elapsed_time(e1) * 1e-3 / reps) / 1e9
+        return out
+
     def bytes_per_step(self):
         w = self.w
         total = 0
@@ -303,6 +329,7 @@ def bench_decode(args, wname):
         run.step()
         torch.cuda.synchronize()
         cpu, parity = cpu_baseline_and_parity(run, args.seed)
+    ceiling = run.read_ceiling()
     ns, tps = run.st.ctx.decode_plan(retr[0], 0) if retr else (0, 0)
     per_launch = layer_bytes(w, False, w.context)
     out = {
@@ -323,7 +350,9 @@ def bench_decode(args, wname):
                      "achieved": per_launch / t_launch / 1e9 if t_launch else None, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": per_launch / t_launch / 1e9 / HBM_PEAK_GBPS if t_launch else None,
                      "bytes_per_launch": per_launch, "avg_launch_us": t_launch * 1e6 if t_launch else None,
-                     "traffic": profiled_traffic("decode_retrieval_%s.txt" % wname)},
+                     "traffic": profiled_traffic("decode_retrieval_%s.txt" % wname),
+                     "streaming_read_GBps": ceiling,
+                     "frac_of_streaming_read": per_launch / t_launch / 1e9 / ceiling["nontemporal_loads"] if t_launch else None},
         "cpu_baseline": cpu, "parity_sample": parity,
     }
     if t_graph is not None:

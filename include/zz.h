@@ -185,6 +185,13 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
 int zz_transport_select(const float *alpha, int n_layers, int n_heads, float sparsity, float omega,
                         uint8_t *layer_is_streaming, double *loss);
 
+/* Measurement aid, not part of the method: streams `bytes` (rounded down to 16 KiB) of DEVICE
+ * memory `buf` through one workgroup per compute unit with the decode kernel's access pattern
+ * and discards them; nontemporal != 0 uses the same non-temporal loads as the decode kernel.
+ * Timed by the caller, it gives the read bandwidth the memory system delivers to that
+ * pattern: the practical ceiling beside the published peak. */
+int zz_probe_read(zz_ctx *ctx, const void *buf, size_t bytes, int nontemporal, void *stream);
+
 const char *zz_strerror(int code);
 /* What the HIP runtime reported for the calling thread's most recent ZZ_EHIP
  * (which kernel, hipGetErrorString text); "" if there was none. */

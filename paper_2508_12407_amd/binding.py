@@ -62,6 +62,7 @@ def _load():
         "zz_decode_plan": (I, [V, I, I, P(I), P(I)]),
         "zz_prefill_tile_counts": (I, [V, I, I, P(I64), P(I64)]),
         "zz_transport_select": (I, [P(C.c_float), I, I, C.c_float, C.c_float, P(C.c_uint8), P(C.c_double)]),
+        "zz_probe_read": (I, [V, V, C.c_size_t, I, V]),
         "zz_strerror": (C.c_char_p, [I]),
         "zz_last_error_detail": (C.c_char_p, []),
     }
@@ -188,6 +189,9 @@ class Context:
         a, b = C.c_int64(), C.c_int64()
         self._chk(lib.zz_prefill_tile_counts(self._h, layer, n_new, C.byref(a), C.byref(b)), "zz_prefill_tile_counts")
         return a.value, b.value
+
+    def probe_read(self, buf, nbytes, nontemporal, stream=None):
+        self._chk(lib.zz_probe_read(self._h, _ptr(buf), nbytes, int(nontemporal), stream), "zz_probe_read")
 
     def tune(self, key, value):
         self._chk(lib.zz_tune(self._h, key, value), "zz_tune")

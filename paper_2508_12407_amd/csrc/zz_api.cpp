@@ -514,6 +514,17 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
   return ZZ_OK;
 }
 
+int zz_probe_read(zz_ctx *ctx, const void *buf, size_t bytes, int nontemporal, void *stream) {
+  if (!ctx || !buf) return ZZ_EINVAL;
+  if (misaligned(buf, 16)) return ZZ_EALIGN;
+  if (bytes < 16 * 1024) return ZZ_ERANGE;
+  // the 4 KiB the kernel may (never, in practice) write to is the start of the split-K partials
+  if (hipError_t e = zz_launch_probe_read(buf, bytes, nontemporal, num_cu(ctx), ctx->ws + ctx->lo.ws_part_o,
+                                          (hipStream_t)stream))
+    return hip_failed("read probe kernel", e);
+  return ZZ_OK;
+}
+
 const char *zz_last_error_detail(void) { return g_detail; }
 
 const char *zz_strerror(int code) {

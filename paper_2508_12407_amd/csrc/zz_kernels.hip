@@ -916,6 +916,34 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
 }
 
 // --------------------------------------------------------------------------
+// Measurement aid: a pure streaming read of a buffer, with the decode kernel's access
+// pattern (one workgroup per compute unit, each wave 16 KiB at a time, 1 KiB per load) and
+// nothing else: what the memory system delivers to this pattern is the practical ceiling
+// the decode kernel is compared with, next to the published peak.
+// --------------------------------------------------------------------------
+template <bool NT>
+__global__ __launch_bounds__(256) void zz_probe_read_kernel(const uint4 *p, size_t n_blocks, uint4 *sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t per = (n_blocks + gridDim.x - 1) / gridDim.x;
+  const size_t b1 = min((size_t)(blockIdx.x + 1) * per, n_blocks);
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (size_t blk = (size_t)blockIdx.x * per + wave; blk < b1; blk += ZZ_WAVES_PER_WG) {
+    const uint4 *src = p + blk * (16 * 64) + lane;
+    uint4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = NT ? load_stream(src + i * 64) : src[i * 64];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      acc.x ^= v[i].x;
+      acc.y ^= v[i].y;
+      acc.z ^= v[i].z;
+      acc.w ^= v[i].w;
+    }
+  }
+  if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u) sink[threadIdx.x] = acc;  // keeps the loads alive
+}
+
+// --------------------------------------------------------------------------
 // Launchers
 // --------------------------------------------------------------------------
 
@@ -992,6 +1020,12 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
 
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s) {
   return launch(zz_zero_kernel, dim3((n + 255) / 256), dim3(256), s, p, n);
+}
+
+hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, int n_wg, void *sink, hipStream_t s) {
+  const size_t n_blocks = bytes / (16 * 1024);
+  if (nontemporal) return launch(zz_probe_read_kernel<true>, dim3(n_wg), dim3(256), s, (const uint4 *)buf, n_blocks, (uint4 *)sink);
+  return launch(zz_probe_read_kernel<false>, dim3(n_wg), dim3(256), s, (const uint4 *)buf, n_blocks, (uint4 *)sink);
 }
 
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {

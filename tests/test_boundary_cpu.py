@@ -198,6 +198,10 @@ def test_entry_point_error_paths_launch_nothing():
     assert ctx.layer_len(7) == E["ERANGE"] and ctx.layer_launches(7) == E["ERANGE"]
     assert L.zz_reset(h) == 0 and ctx.layer_len(0) == 0
     assert L.zz_tune(h, 99, 1) == E["EINVAL"] and L.zz_tune(h, zb.TUNE_DECODE_SPLITS, 129) == E["ERANGE"]
+    assert L.zz_probe_read(h, None, 1 << 20, 1, None) == E["EINVAL"]
+    assert L.zz_probe_read(None, A, 1 << 20, 1, None) == E["EINVAL"]
+    assert L.zz_probe_read(h, A + 4, 1 << 20, 1, None) == E["EALIGN"]
+    assert L.zz_probe_read(h, A, 1000, 0, None) == E["ERANGE"]
     assert L.zz_reset(None) == E["EINVAL"] and L.zz_destroy(None) == E["EINVAL"]
 
 
