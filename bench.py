@@ -166,6 +166,20 @@ class DecodeRun:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    def per_step_events(self, steps):
+        """Median and minimum step time from HIP events around each step (same stream)."""
+        torch = self.torch
+        evs = []
+        for _ in range(steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            self.step()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)
+        return {"median_ms": ms[len(ms) // 2], "min_ms": ms[0], "max_ms": ms[-1]}
+
     def timed_graph(self, steps, warmup):
         """The same step captured once into a HIP graph and replayed."""
         torch = self.torch
@@ -289,6 +303,7 @@ def cpu_baseline_and_parity(run, seed):
     step_s = sum(t_kind[k] / n_kind[k] * n_units[k] for k in t_kind)
     t_cpu = sum(t_kind.values())
     return dict(value=step_s / w.batch * 1e6, unit="us/token", cores=threads, kind="oracle",
+                measured_on_sample_s=t_cpu, extrapolated=True,
                 sample=f"{len(units)} (layer,batch,kv-head) units of this workload "
                        f"({n_kind.get(False, 0)} retrieval, {n_kind.get(True, 0)} streaming: every unit of the "
                        f"sampled layers), {t_cpu:.2f} s wall on {threads} threads, extrapolated by unit count "
@@ -319,6 +334,7 @@ def bench_decode(args, wname):
         torch.cuda.synchronize()
         del src, dst
     t_step = run.timed(args.steps, args.warmup)
+    step_events = run.per_step_events(args.steps)
     t_sep = run.timed(args.steps, args.warmup, mode="separate")
     t_attn = run.timed(args.steps, args.warmup, mode="attention")
     t_graph = None if args.no_graph else run.timed_graph(args.steps, args.warmup)
@@ -343,6 +359,7 @@ def bench_decode(args, wname):
                    "launch": "plain stream launches, one zz_decode_step (append fused into the attention launch) per layer",
                    "retrieval_split_k": {"splits": ns, "tiles_per_split": tps}},
         "achieved_GBps": nbytes / t_step / 1e9, "algorithmic_bytes_per_step": nbytes,
+        "step_by_hip_events": step_events,
         "attention_only": {"us_per_token": t_attn / w.batch * 1e6, "GBps": nbytes / t_attn / 1e9},
         "separate_append": {"us_per_token": t_sep / w.batch * 1e6, "GBps": nbytes / t_sep / 1e9,
                             "note": "zz_kv_append + zz_attn_decode per layer (two launches)"},

@@ -38,6 +38,8 @@ def bench_prefill(args, wname):
     keep_out = {}
     sp = st.stream_ptr()
 
+    kind_counts = {False: [0, 0], True: [0, 0]}
+
     def one_prompt(record=False, time_kernel=None):
         st.ctx.reset()
         vis = cau = 0
@@ -47,6 +49,8 @@ def bench_prefill(args, wname):
                     a, b_ = st.ctx.prefill_tile_counts(l, C)
                     vis += a
                     cau += b_
+                    kind_counts[bool(lmask[l])][0] += a
+                    kind_counts[bool(lmask[l])][1] += b_
                 if time_kernel is not None and time_kernel[0] == (c, l):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
@@ -131,7 +135,12 @@ def bench_prefill(args, wname):
                    "head_dim": D, "batch": B, "prompt": T, "chunk": C, "sink": w.sink, "window": w.window,
                    "streaming_layers": w.n_streaming_layers, "step": "whole prompt: attention + append per chunk per layer"},
         "algorithmic_flop_per_step": flop, "us_per_prompt_token": t_step / (T * B) * 1e6,
-        "skipped_tile_fraction": 1.0 - vis / cau, "tile": "32 keys x 64 query positions (x4 heads of the KV group)",
+        "skipped_tile_fraction": 1.0 - vis / cau,
+        "skipped_tile_fraction_by_kind": {"retrieval": 1.0 - kind_counts[False][0] / max(kind_counts[False][1], 1),
+                                          "streaming": 1.0 - kind_counts[True][0] / max(kind_counts[True][1], 1)},
+        "tile": "32 keys x 64 query positions x 2 heads (one workgroup's share of a KV tile)",
+        # every visited (workgroup, tile) pair is computed in full: scores and P V for 64 x 2 x 32 pairs
+        "tile_granular_flop_per_step": vis * 64 * 2 * 32 * 4 * D,
         "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128,4,3>, retrieval layer, last 4096-token chunk of 65536",
                      "achieved": flop_last / t_kernel / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_last / t_kernel / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop_per_launch": flop_last,
