@@ -65,7 +65,7 @@ typedef struct zz_config {
   int32_t n_q_heads;  /* Hq, multiple of n_kv_heads, Hq / Hkv <= 16                       */
   int32_t n_kv_heads; /* Hkv <= ZZ_MAX_KV_HEADS                                           */
   int32_t head_dim;   /* D: 64 or 128                                                     */
-  int32_t batch;      /* B >= 1                                                           */
+  int32_t batch;      /* 1 <= B <= 65535                                                  */
   int32_t max_ctx;    /* capacity of a retrieval cache, tokens                            */
   int32_t sink;       /* S >= 0  (Section 3.3)                                            */
   int32_t window;     /* W >= 1  (Section 3.3), includes the query's own position         */

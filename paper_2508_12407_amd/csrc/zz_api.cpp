@@ -47,6 +47,7 @@ int validate(const zz_config *c) {
   if (!(c->softmax_scale >= 0.0f) || !std::isfinite(c->softmax_scale)) return ZZ_EINVAL;
   if (c->head_dim != 64 && c->head_dim != 128) return ZZ_EUNSUPPORTED;
   if (c->n_kv_heads > ZZ_MAX_KV_HEADS) return ZZ_EUNSUPPORTED;
+  if (c->batch > 65535) return ZZ_EUNSUPPORTED;  // the batch index is a grid dimension
   if (c->n_q_heads % c->n_kv_heads != 0) return ZZ_EINVAL;
   if (c->n_q_heads / c->n_kv_heads > 16) return ZZ_EUNSUPPORTED;
   if ((int64_t)c->sink + c->window > (int64_t)1 << 30 || c->max_ctx > (1 << 30)) return ZZ_EUNSUPPORTED;

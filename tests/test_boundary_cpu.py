@@ -51,7 +51,7 @@ def test_config_validation_codes():
     bad = [
         (dict(L=0), E["EINVAL"]), (dict(B=0), E["EINVAL"]), (dict(W=0), E["EINVAL"]), (dict(S=-1), E["EINVAL"]),
         (dict(max_ctx=0), E["EINVAL"]), (dict(Hq=5), E["EINVAL"]), (dict(D=96), E["EUNSUPPORTED"]),
-        (dict(Hq=34, Hkv=2), E["EUNSUPPORTED"]), (dict(Hq=128, Hkv=128), E["EUNSUPPORTED"]),
+        (dict(Hq=34, Hkv=2), E["EUNSUPPORTED"]), (dict(B=65536), E["EUNSUPPORTED"]), (dict(Hq=128, Hkv=128), E["EUNSUPPORTED"]),
         (dict(layout=7), E["EINVAL"]), (dict(scale=-1.0), E["EINVAL"]), (dict(scale=float("nan")), E["EINVAL"]),
         (dict(lmask=None), E["ESTATE"]),                                   # zigzag needs the layer mask
         (dict(layout=zb.ZZ_MIXED, lmask=(0, 1), hmask=None), E["ESTATE"]),  # mixed needs the head mask
