@@ -28,7 +28,13 @@
  *   - Return value: 0 (ZZ_OK) or a negative ZZ_E* code.  All argument checks run on
  *     the host before anything is launched; a call that fails has launched nothing
  *     and changed no length.  n_new == 0 is a successful no-op.
- *   - All B sequences of a batch share one length per layer.
+ *   - Every sequence of the batch has its own length per layer.  The batched calls
+ *     advance all B sequences by the same number of tokens, each from its own length;
+ *     the *_seq calls advance one sequence, which is how prompts of different lengths
+ *     enter a batch.  While all lengths of a layer are equal a batched call is one launch
+ *     per head kind; zz_kv_append and zz_attn_prefill on unequal lengths issue one per
+ *     sequence, zz_attn_decode and zz_decode_step stay at one launch per head kind
+ *     (batches of at most ZZ_MAX_RAGGED_BATCH sequences, else ZZ_EUNSUPPORTED).
  *   - A context must not be used from two host threads at once.
  */
 #ifndef ZZ_H
@@ -44,6 +50,7 @@ extern "C" {
 #define ZZ_TILE_SLOTS 32   /* cache slots per KV tile                                   */
 #define ZZ_MAX_KV_HEADS 64 /* upper bound on n_kv_heads                                  */
 #define ZZ_MAX_SPLITS 128  /* upper bound on split-K partials per (batch, query head)    */
+#define ZZ_MAX_RAGGED_BATCH 256 /* largest batch whose sequences may differ in length at decode */
 
 enum {
   ZZ_OK = 0,
@@ -95,6 +102,9 @@ int zz_reset(zz_ctx *ctx); /* all layer lengths := 0 */
  * ZZ_ENOSPC if the layer's length would exceed max_ctx (lengths of all layers, also
  * all-streaming ones, are bounded by max_ctx). */
 int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new, void *stream);
+/* The same for sequence b alone: k_new, v_new: DEVICE [1, n_new, Hkv, D]; only that
+ * sequence's length changes.  ZZ_ERANGE if b is not in [0, B). */
+int zz_kv_append_seq(zz_ctx *ctx, int layer, int b, const void *k_new, const void *v_new, int n_new, void *stream);
 
 /* Attention for n_new new query positions [len, len + n_new) of layer `layer`, where
  * len = zz_layer_len(layer), over the cached tokens followed by (k_new, v_new)
@@ -104,10 +114,15 @@ int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, i
  * 1 <= n_new <= max_chunk.  Uses the workspace; calls on one context must be stream-ordered. */
 int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new,
                     int n_new, void *out, void *stream);
+/* The same for sequence b alone (query positions [zz_seq_len(b), zz_seq_len(b) + n_new)):
+ * q, out: DEVICE [1, n_new, Hq, D]; k_new, v_new: DEVICE [1, n_new, Hkv, D].  Follow it with
+ * zz_kv_append_seq.  ZZ_ERANGE if b is not in [0, B). */
+int zz_attn_prefill_seq(zz_ctx *ctx, int layer, int b, const void *q, const void *k_new, const void *v_new,
+                        int n_new, void *out, void *stream);
 
 /* Attention for the newest cached position of layer `layer` (Section 1: decoding
  * phase): call after zz_kv_append(..., 1).  q, out: DEVICE [B, Hq, D].
- * ZZ_ESTATE if the layer is empty.  Uses the workspace. */
+ * ZZ_ESTATE if a sequence of the layer is empty.  Uses the workspace. */
 int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream);
 
 /* One decode step of a layer in a single launch per head kind: appends the newest
@@ -120,10 +135,15 @@ int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *strea
 int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
                    void *stream);
 
-/* Tokens appended to the layer so far, or a negative error code. */
+/* Tokens appended to the layer so far (of its longest sequence, if they differ), or a
+ * negative error code. */
 int64_t zz_layer_len(const zz_ctx *ctx, int layer);
-/* Overwrite a layer's length (restoring a snapshot of the arena). 0 <= len <= max_ctx. */
+/* Overwrite the length of every sequence of a layer (restoring a snapshot of the arena).
+ * 0 <= len <= max_ctx. */
 int zz_set_layer_len(zz_ctx *ctx, int layer, int64_t len);
+/* The same per sequence.  ZZ_ERANGE if b is not in [0, B). */
+int64_t zz_seq_len(const zz_ctx *ctx, int layer, int b);
+int zz_set_seq_len(zz_ctx *ctx, int layer, int b, int64_t len);
 
 /* Attention launches zz_attn_decode issues for this layer: 1 for a zigzag layer
  * (Section 2.2), 2 for a mixed layer holding both kinds of head (Section 2.1). */
@@ -159,7 +179,10 @@ enum {
 int zz_tune(zz_ctx *ctx, int key, int value);
 
 /* Split count and tiles per split the next zz_attn_decode would use for group
- * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty. */
+ * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty.
+ * With unequal sequence lengths one tiles-per-split value serves the whole launch,
+ * sequence b takes ceil(its tiles / tiles_per_split) workgroups per head, and *n_splits
+ * is the largest of those counts. */
 int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
 
 /* Pure host arithmetic: how many (workgroup, 32-key tile) visits the next

@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_PKG, "libzz.so")
 ZZ_ZIGZAG, ZZ_MIXED = 0, 1
 ZZ_TILE_SLOTS = 32
 ZZ_MAX_SPLITS = 128
+ZZ_MAX_RAGGED_BATCH = 256
 ERR = dict(OK=0, EINVAL=-1, ERANGE=-2, ENOSPC=-3, EALIGN=-4, ESTATE=-5, EUNSUPPORTED=-6, EHIP=-7)
 TUNE_DECODE_WG_PER_CU, TUNE_DECODE_SPLITS, TUNE_NUM_CU = 1, 2, 3
 
@@ -53,6 +54,10 @@ def _load():
         "zz_attn_prefill": (I, [V, I, V, V, V, I, V, V]),
         "zz_attn_decode": (I, [V, I, V, V, V]),
         "zz_decode_step": (I, [V, I, V, V, V, V, V]),
+        "zz_kv_append_seq": (I, [V, I, I, V, V, I, V]),
+        "zz_attn_prefill_seq": (I, [V, I, I, V, V, V, I, V, V]),
+        "zz_seq_len": (I64, [V, I, I]),
+        "zz_set_seq_len": (I, [V, I, I, I64]),
         "zz_layer_len": (I64, [V, I]),
         "zz_set_layer_len": (I, [V, I, I64]),
         "zz_layer_launches": (I, [V, I]),
@@ -165,6 +170,19 @@ class Context:
     def attn_prefill(self, layer, q, k_new, v_new, n_new, out, stream=None):
         self._chk(lib.zz_attn_prefill(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), n_new, _ptr(out), stream),
                   "zz_attn_prefill")
+
+    def kv_append_seq(self, layer, b, k_new, v_new, n_new, stream=None):
+        self._chk(lib.zz_kv_append_seq(self._h, layer, b, _ptr(k_new), _ptr(v_new), n_new, stream), "zz_kv_append_seq")
+
+    def attn_prefill_seq(self, layer, b, q, k_new, v_new, n_new, out, stream=None):
+        self._chk(lib.zz_attn_prefill_seq(self._h, layer, b, _ptr(q), _ptr(k_new), _ptr(v_new), n_new, _ptr(out),
+                                          stream), "zz_attn_prefill_seq")
+
+    def seq_len(self, layer, b):
+        return int(lib.zz_seq_len(self._h, layer, b))
+
+    def set_seq_len(self, layer, b, n):
+        self._chk(lib.zz_set_seq_len(self._h, layer, b, n), "zz_set_seq_len")
 
     def attn_decode(self, layer, q, out, stream=None):
         self._chk(lib.zz_attn_decode(self._h, layer, _ptr(q), _ptr(out), stream), "zz_attn_decode")

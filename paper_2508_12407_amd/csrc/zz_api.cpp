@@ -25,7 +25,18 @@ struct Layer {
   Group grp[2];  // 0: retrieval heads, 1: streaming heads
   uint8_t head_group[ZZ_MAX_KV_HEADS] = {0};
   uint8_t head_index[ZZ_MAX_KV_HEADS] = {0};
-  int64_t len = 0;
+  std::vector<int64_t> len;  // tokens appended so far, per sequence
+
+  bool uniform() const {
+    for (int64_t v : len)
+      if (v != len[0]) return false;
+    return true;
+  }
+  int64_t longest() const {
+    int64_t m = 0;
+    for (int64_t v : len) m = v > m ? v : m;
+    return m;
+  }
 };
 
 struct Layout {
@@ -68,6 +79,7 @@ void build_layout(const zz_config *c, Layout *lo) {
   size_t off = 0;
   for (int l = 0; l < c->n_layers; ++l) {
     Layer &L = lo->layers[l];
+    L.len.assign(c->batch, 0);
     L.grp[0].streaming = false;
     L.grp[1].streaming = true;
     for (int g = 0; g < c->n_kv_heads; ++g) {
@@ -124,9 +136,10 @@ struct zz_ctx {
 
 namespace {
 
-zz_group_dev dev_group(const zz_ctx *ctx, const Group &G) {
+// The group's region as the kernels see it, starting at sequence b0.
+zz_group_dev dev_group(const zz_ctx *ctx, const Group &G, int b0 = 0) {
   zz_group_dev d;
-  d.base = ctx->arena + G.base;
+  d.base = ctx->arena + G.base + (size_t)b0 * G.n_heads * G.n_tiles * kv_tile_bytes(ctx->cfg.head_dim);
   d.n_heads = G.n_heads;
   d.n_tiles = G.n_tiles;
   d.streaming = G.streaming ? 1 : 0;
@@ -190,6 +203,51 @@ void plan_decode(const zz_ctx *ctx, int cu, const Group &G, int64_t len, int *n_
   *tiles_per_split = (int)tps;
 }
 
+// Split-K plan for sequences of different lengths (len[b]: tokens the attention of sequence
+// b sees).  One tiles-per-split value for the whole launch; sequence b gets
+// ceil(tiles_b / tps) workgroups per head.  The kernel runs one workgroup per compute unit,
+// so a launch with more workgroups than the chip holds would pay a second round for a few
+// stragglers: tps is the smallest value whose workgroups fit in one round (if the batch
+// allows it at all), which also equalises the work per workgroup as far as whole tiles can.
+// Returns the workgroups per head; first_wg[0..B] are the prefix sums.
+int plan_decode_ragged(const zz_ctx *ctx, int cu, const Group &G, const std::vector<int64_t> &len, uint16_t *first_wg,
+                       int *tiles_per_split) {
+  const int B = (int)len.size();
+  std::vector<int64_t> tiles(B);
+  int64_t total = 0, longest = 0;
+  for (int b = 0; b < B; ++b) {
+    tiles[b] = ceil_div(occupied(ctx, G, len[b]), ZZ_TILE_SLOTS);
+    total += tiles[b];
+    longest = tiles[b] > longest ? tiles[b] : longest;
+  }
+  auto wgs = [&](int64_t tps) {
+    int64_t n = 0;
+    for (int b = 0; b < B; ++b) n += ceil_div(tiles[b], tps);
+    return n;
+  };
+  int64_t tps;
+  if (ctx->tune_splits > 0) {
+    tps = ceil_div(longest, ctx->tune_splits);
+  } else {
+    int64_t room = (int64_t)cu * ctx->tune_wg_per_cu / G.n_heads;  // workgroups per head in one round
+    if (room < B) room = B;                                         // every sequence needs one anyway
+    int64_t lo = ceil_div(total, room), hi = longest;               // wgs(hi) == B <= room
+    if (lo < 4 * ZZ_WAVES_PER_WG) lo = 4 * ZZ_WAVES_PER_WG;         // short caches stay unsplit, as in plan_decode
+    if (hi < lo) hi = lo;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) / 2;
+      if (wgs(mid) <= room) hi = mid; else lo = mid + 1;
+    }
+    tps = lo;
+  }
+  if (tps < 1) tps = 1;
+  if (ceil_div(longest, tps) > ZZ_MAX_SPLITS) tps = ceil_div(longest, ZZ_MAX_SPLITS);
+  first_wg[0] = 0;
+  for (int b = 0; b < B; ++b) first_wg[b + 1] = (uint16_t)(first_wg[b] + ceil_div(tiles[b], tps));
+  *tiles_per_split = (int)tps;
+  return first_wg[B];
+}
+
 }  // namespace
 
 extern "C" {
@@ -249,21 +307,36 @@ int zz_destroy(zz_ctx *ctx) {
 
 int zz_reset(zz_ctx *ctx) {
   if (!ctx) return ZZ_EINVAL;
-  for (auto &L : ctx->lo.layers) L.len = 0;
+  for (auto &L : ctx->lo.layers) L.len.assign(ctx->cfg.batch, 0);
   return ZZ_OK;
 }
 
 int64_t zz_layer_len(const zz_ctx *ctx, int layer) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
-  return ctx->lo.layers[layer].len;
+  return ctx->lo.layers[layer].longest();
 }
 
 int zz_set_layer_len(zz_ctx *ctx, int layer, int64_t len) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
   if (len < 0 || len > ctx->cfg.max_ctx) return ZZ_ERANGE;
-  ctx->lo.layers[layer].len = len;
+  ctx->lo.layers[layer].len.assign(ctx->cfg.batch, len);
+  return ZZ_OK;
+}
+
+int64_t zz_seq_len(const zz_ctx *ctx, int layer, int b) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (b < 0 || b >= ctx->cfg.batch) return ZZ_ERANGE;
+  return ctx->lo.layers[layer].len[b];
+}
+
+int zz_set_seq_len(zz_ctx *ctx, int layer, int b, int64_t len) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (b < 0 || b >= ctx->cfg.batch || len < 0 || len > ctx->cfg.max_ctx) return ZZ_ERANGE;
+  ctx->lo.layers[layer].len[b] = len;
   return ZZ_OK;
 }
 
@@ -328,38 +401,136 @@ int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *
   if (rc != ZZ_OK) return rc;
   if (group < 0 || group > 1 || !n_splits || !tiles_per_split) return ZZ_EINVAL;
   const Layer &L = ctx->lo.layers[layer];
-  plan_decode(ctx, num_cu(const_cast<zz_ctx *>(ctx)), L.grp[group], L.len, n_splits, tiles_per_split);
+  const int cu = num_cu(const_cast<zz_ctx *>(ctx));
+  if (L.uniform()) {
+    plan_decode(ctx, cu, L.grp[group], L.len[0], n_splits, tiles_per_split);
+    return ZZ_OK;
+  }
+  *n_splits = *tiles_per_split = 0;
+  if (L.grp[group].n_heads == 0) return ZZ_OK;
+  if (ctx->cfg.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
+  uint16_t first_wg[ZZ_MAX_RAGGED_BATCH + 1];
+  plan_decode_ragged(ctx, cu, L.grp[group], L.len, first_wg, tiles_per_split);
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    if (first_wg[b + 1] - first_wg[b] > *n_splits) *n_splits = first_wg[b + 1] - first_wg[b];
   return ZZ_OK;
 }
 
-int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new, void *stream) {
-  int rc = check_layer(ctx, layer);
-  if (rc != ZZ_OK) return rc;
-  if (n_new < 0) return ZZ_ERANGE;
-  if (n_new == 0) return ZZ_OK;
-  if (!k_new || !v_new) return ZZ_EINVAL;
-  if (misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
-  Layer &L = ctx->lo.layers[layer];
+namespace {
+
+// Appends n_new tokens to sequences [b0, b0 + nb) of the layer, which share the length
+// `len`; k_new, v_new point at the rows of sequence b0.
+int append_run(zz_ctx *ctx, Layer &L, int b0, int nb, int64_t len, const void *k_new, const void *v_new, int n_new,
+               void *stream) {
   const zz_config &c = ctx->cfg;
-  if (L.len + n_new > c.max_ctx) return ZZ_ENOSPC;  // the length counter itself is bounded by max_ctx
   zz_append_params p;
   std::memset(&p, 0, sizeof(p));
   p.k_new = k_new;
   p.v_new = v_new;
-  p.grp[0] = dev_group(ctx, L.grp[0]);
-  p.grp[1] = dev_group(ctx, L.grp[1]);
+  p.grp[0] = dev_group(ctx, L.grp[0], b0);
+  p.grp[1] = dev_group(ctx, L.grp[1], b0);
   std::memcpy(p.head_group, L.head_group, sizeof(p.head_group));
   std::memcpy(p.head_index, L.head_index, sizeof(p.head_index));
-  p.len = L.len;
+  p.len = len;
   p.n_new = n_new;
-  p.batch = c.batch;
+  p.batch = nb;
   p.n_kv_heads = c.n_kv_heads;
   p.head_dim = c.head_dim;
   p.sink = c.sink;
   p.window = c.window;
   p.only_group = -1;
   if (hipError_t e = zz_launch_append(p, (hipStream_t)stream)) return hip_failed("append kernel", e);
-  L.len += n_new;
+  return ZZ_OK;
+}
+
+// Attention of n_new new positions for sequences [b0, b0 + nb), which share the length
+// n_past; all four tensors point at the rows of sequence b0.
+int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, const void *q, const void *k_new,
+                const void *v_new, int n_new, void *out, void *stream) {
+  const zz_config &c = ctx->cfg;
+  zz_stage_params sp;
+  std::memset(&sp, 0, sizeof(sp));
+  sp.k_new = k_new;
+  sp.v_new = v_new;
+  sp.stage_tiles = ctx->lo.stage_tiles;
+  sp.stage = ctx->ws + ctx->lo.ws_stage + (size_t)b0 * c.n_kv_heads * sp.stage_tiles * kv_tile_bytes(c.head_dim);
+  sp.n_new = n_new;
+  sp.batch = nb;
+  sp.n_kv_heads = c.n_kv_heads;
+  sp.head_dim = c.head_dim;
+  if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
+  for (int k = 0; k < 2; ++k) {
+    const Group &G = L.grp[k];
+    if (G.n_heads == 0) continue;
+    zz_prefill_params p;
+    std::memset(&p, 0, sizeof(p));
+    p.grp = dev_group(ctx, G, b0);
+    std::memcpy(p.heads, G.heads, sizeof(p.heads));
+    p.q = q;
+    p.out = out;
+    p.stage = sp.stage;
+    p.stage_tiles = sp.stage_tiles;
+    p.n_past = (int)n_past;
+    p.n_new = n_new;
+    p.batch = nb;
+    p.n_q_heads = c.n_q_heads;
+    p.n_kv_heads = c.n_kv_heads;
+    p.head_dim = c.head_dim;
+    p.group_size = c.n_q_heads / c.n_kv_heads;
+    p.sink = c.sink;
+    p.window = c.window;
+    p.scale_log2e = ctx->scale * 1.4426950408889634f;
+    if (hipError_t e = zz_launch_prefill(p, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+  }
+  return ZZ_OK;
+}
+
+inline const void *rows_of(const void *base, int b, int n_new, int heads, int D) {
+  return base ? (const char *)base + (size_t)b * n_new * heads * D * 2 : nullptr;
+}
+
+int check_chunk(const zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new) {
+  int rc = check_layer(ctx, layer);
+  if (rc != ZZ_OK) return rc;
+  if (n_new < 0) return ZZ_ERANGE;
+  if (n_new == 0) return ZZ_OK;
+  if (!k_new || !v_new) return ZZ_EINVAL;
+  if (misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
+  return ZZ_OK;
+}
+
+}  // namespace
+
+int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, int n_new, void *stream) {
+  int rc = check_chunk(ctx, layer, k_new, v_new, n_new);
+  if (rc != ZZ_OK || n_new == 0) return rc;
+  Layer &L = ctx->lo.layers[layer];
+  const zz_config &c = ctx->cfg;
+  if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;  // the length counter itself is bounded by max_ctx
+  if (L.uniform()) {
+    rc = append_run(ctx, L, 0, c.batch, L.len[0], k_new, v_new, n_new, stream);
+    if (rc != ZZ_OK) return rc;
+  } else {
+    for (int b = 0; b < c.batch; ++b) {
+      rc = append_run(ctx, L, b, 1, L.len[b], rows_of(k_new, b, n_new, c.n_kv_heads, c.head_dim),
+                      rows_of(v_new, b, n_new, c.n_kv_heads, c.head_dim), n_new, stream);
+      if (rc != ZZ_OK) return rc;  // launches already issued only wrote slots past the unchanged lengths
+    }
+  }
+  for (auto &v : L.len) v += n_new;
+  return ZZ_OK;
+}
+
+int zz_kv_append_seq(zz_ctx *ctx, int layer, int b, const void *k_new, const void *v_new, int n_new, void *stream) {
+  int rc = check_chunk(ctx, layer, k_new, v_new, n_new);
+  if (rc != ZZ_OK) return rc;
+  if (b < 0 || b >= ctx->cfg.batch) return ZZ_ERANGE;
+  if (n_new == 0) return ZZ_OK;
+  Layer &L = ctx->lo.layers[layer];
+  if (L.len[b] + n_new > ctx->cfg.max_ctx) return ZZ_ENOSPC;
+  rc = append_run(ctx, L, b, 1, L.len[b], k_new, v_new, n_new, stream);
+  if (rc != ZZ_OK) return rc;
+  L.len[b] += n_new;
   return ZZ_OK;
 }
 
@@ -374,9 +545,14 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
   if (misaligned(q, 16) || misaligned(out, 16) || misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
   Layer &L = ctx->lo.layers[layer];
   const zz_config &c = ctx->cfg;
-  if (fused && L.len + 1 > c.max_ctx) return ZZ_ENOSPC;
-  const int64_t len = L.len + (fused ? 1 : 0);  // tokens the attention sees
-  if (len <= 0) return ZZ_ESTATE;
+  if (fused && L.longest() + 1 > c.max_ctx) return ZZ_ENOSPC;
+  std::vector<int64_t> seen(L.len);  // tokens the attention of each sequence sees
+  for (auto &v : seen) {
+    v += fused ? 1 : 0;
+    if (v <= 0) return ZZ_ESTATE;
+  }
+  const bool uniform = L.uniform();
+  if (!uniform && c.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
   const int cu = num_cu(ctx);
   int *counters = (int *)(ctx->ws + ctx->lo.ws_counters);
   if (!ctx->counters_zeroed) {
@@ -387,8 +563,9 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
   for (int k = 0; k < 2; ++k) {
     const Group &G = L.grp[k];
     if (G.n_heads == 0) continue;
-    zz_decode_params p;
-    std::memset(&p, 0, sizeof(p));
+    zz_decode_ragged_params rp;
+    std::memset(&rp, 0, sizeof(rp));
+    zz_decode_params &p = rp.u;
     p.grp = dev_group(ctx, G);
     std::memcpy(p.heads, G.heads, sizeof(p.heads));
     p.q = q;
@@ -398,19 +575,30 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
     p.counters = counters;
     p.k_new = k_new;
     p.v_new = v_new;
-    p.new_slot = fused ? (int32_t)slot_rule(G.streaming, len - 1, c.sink, c.window) : -1;
-    p.n_valid = (int)occupied(ctx, G, len);
-    p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
-    plan_decode(ctx, cu, G, len, &p.n_splits, &p.tiles_per_split);
     p.batch = c.batch;
     p.n_q_heads = c.n_q_heads;
     p.n_kv_heads = c.n_kv_heads;
     p.head_dim = c.head_dim;
     p.group_size = c.n_q_heads / c.n_kv_heads;
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    if (hipError_t e = zz_launch_decode(p, (hipStream_t)stream)) return hip_failed("decode kernel", e);
+    if (uniform) {
+      const int64_t len = seen[0];
+      p.new_slot = fused ? (int32_t)slot_rule(G.streaming, len - 1, c.sink, c.window) : -1;
+      p.n_valid = (int)occupied(ctx, G, len);
+      p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
+      plan_decode(ctx, cu, G, len, &p.n_splits, &p.tiles_per_split);
+      if (hipError_t e = zz_launch_decode(p, (hipStream_t)stream)) return hip_failed("decode kernel", e);
+    } else {
+      p.new_slot = fused ? 0 : -1;  // only the sign is read: each sequence's slot follows from its length
+      rp.sink = c.sink;
+      rp.window = c.window;
+      for (int b = 0; b < c.batch; ++b) rp.seq_len[b] = (uint32_t)seen[b];
+      const int total_wg = plan_decode_ragged(ctx, cu, G, seen, rp.first_wg, &p.tiles_per_split);
+      if (hipError_t e = zz_launch_decode_ragged(rp, total_wg, (hipStream_t)stream))
+        return hip_failed("decode kernel (per-sequence lengths)", e);
+    }
   }
-  L.len = len;
+  L.len = seen;
   return ZZ_OK;
 }
 
@@ -424,53 +612,45 @@ int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, con
   return decode_impl(ctx, layer, q, k_new, v_new, out, stream);
 }
 
-int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, int n_new,
-                    void *out, void *stream) {
+static int check_prefill(const zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, int n_new,
+                         const void *out) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
   if (n_new < 0) return ZZ_ERANGE;
   if (n_new == 0) return ZZ_OK;
   if (!q || !k_new || !v_new || !out) return ZZ_EINVAL;
   if (misaligned(q, 16) || misaligned(k_new, 16) || misaligned(v_new, 16) || misaligned(out, 16)) return ZZ_EALIGN;
+  if (n_new > ctx->cfg.max_chunk) return ZZ_ERANGE;
+  return ZZ_OK;
+}
+
+int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, int n_new,
+                    void *out, void *stream) {
+  int rc = check_prefill(ctx, layer, q, k_new, v_new, n_new, out);
+  if (rc != ZZ_OK || n_new == 0) return rc;
   const zz_config &c = ctx->cfg;
-  if (n_new > c.max_chunk) return ZZ_ERANGE;
-  Layer &L = ctx->lo.layers[layer];
-  if (L.len + n_new > c.max_ctx) return ZZ_ENOSPC;
-  zz_stage_params sp;
-  std::memset(&sp, 0, sizeof(sp));
-  sp.k_new = k_new;
-  sp.v_new = v_new;
-  sp.stage = ctx->ws + ctx->lo.ws_stage;
-  sp.stage_tiles = ctx->lo.stage_tiles;
-  sp.n_new = n_new;
-  sp.batch = c.batch;
-  sp.n_kv_heads = c.n_kv_heads;
-  sp.head_dim = c.head_dim;
-  if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
-  for (int k = 0; k < 2; ++k) {
-    const Group &G = L.grp[k];
-    if (G.n_heads == 0) continue;
-    zz_prefill_params p;
-    std::memset(&p, 0, sizeof(p));
-    p.grp = dev_group(ctx, G);
-    std::memcpy(p.heads, G.heads, sizeof(p.heads));
-    p.q = q;
-    p.out = out;
-    p.stage = sp.stage;
-    p.stage_tiles = sp.stage_tiles;
-    p.n_past = (int)L.len;
-    p.n_new = n_new;
-    p.batch = c.batch;
-    p.n_q_heads = c.n_q_heads;
-    p.n_kv_heads = c.n_kv_heads;
-    p.head_dim = c.head_dim;
-    p.group_size = c.n_q_heads / c.n_kv_heads;
-    p.sink = c.sink;
-    p.window = c.window;
-    p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    if (hipError_t e = zz_launch_prefill(p, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+  const Layer &L = ctx->lo.layers[layer];
+  if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;
+  if (L.uniform()) return prefill_run(ctx, L, 0, c.batch, L.len[0], q, k_new, v_new, n_new, out, stream);
+  for (int b = 0; b < c.batch; ++b) {
+    rc = prefill_run(ctx, L, b, 1, L.len[b], rows_of(q, b, n_new, c.n_q_heads, c.head_dim),
+                     rows_of(k_new, b, n_new, c.n_kv_heads, c.head_dim),
+                     rows_of(v_new, b, n_new, c.n_kv_heads, c.head_dim), n_new,
+                     (void *)rows_of(out, b, n_new, c.n_q_heads, c.head_dim), stream);
+    if (rc != ZZ_OK) return rc;
   }
   return ZZ_OK;
+}
+
+int zz_attn_prefill_seq(zz_ctx *ctx, int layer, int b, const void *q, const void *k_new, const void *v_new, int n_new,
+                        void *out, void *stream) {
+  int rc = check_prefill(ctx, layer, q, k_new, v_new, n_new, out);
+  if (rc != ZZ_OK) return rc;
+  if (b < 0 || b >= ctx->cfg.batch) return ZZ_ERANGE;
+  if (n_new == 0) return ZZ_OK;
+  const Layer &L = ctx->lo.layers[layer];
+  if (L.len[b] + n_new > ctx->cfg.max_ctx) return ZZ_ENOSPC;
+  return prefill_run(ctx, L, b, 1, L.len[b], q, k_new, v_new, n_new, out, stream);
 }
 
 int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *visited, int64_t *causal) {
@@ -480,34 +660,37 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
   const zz_config &c = ctx->cfg;
   if (n_new < 1 || n_new > c.max_chunk) return ZZ_ERANGE;
   const Layer &L = ctx->lo.layers[layer];
-  const int64_t n_past = L.len, S = c.sink, W = c.window;
+  const int64_t S = c.sink, W = c.window;
   const int G = c.n_q_heads / c.n_kv_heads;
   const int Gc = zz_prefill_heads_per_wave(G);
   const int QB = ZZ_WAVES_PER_WG * 16 * (ZZ_PREFILL_NB / Gc);  // query positions per workgroup, as the launcher chooses
   int64_t vis = 0, cau = 0;
-  for (int k = 0; k < 2; ++k) {
-    const Group &Gr = L.grp[k];
-    if (Gr.n_heads == 0) continue;
-    const int64_t wgs_per_range = (int64_t)c.batch * Gr.n_heads * (G / Gc);
-    const int64_t n_ct = ceil_div(occupied(ctx, Gr, n_past), ZZ_TILE_SLOTS);  // every occupied cached tile is read
-    for (int64_t iq0 = 0; iq0 < n_new; iq0 += QB) {
-      const int64_t iq_last = (iq0 + QB < n_new ? iq0 + QB : n_new) - 1;
-      const int64_t I_lo = n_past + iq0, k_hi = iq_last / ZZ_TILE_SLOTS;
-      // the causal lower triangle at this granularity: every cached position plus staged tiles up to the diagonal
-      const int64_t all = ceil_div(n_past, ZZ_TILE_SLOTS) + k_hi + 1;
-      int64_t ks_end = 0, kw_begin = 0;
-      if (Gr.streaming) {
-        if (n_past < S) {
-          const int64_t e = (S - 1 - n_past) / ZZ_TILE_SLOTS;
-          ks_end = (e < k_hi ? e : k_hi) + 1;
+  for (int b = 0; b < c.batch; ++b) {
+    const int64_t n_past = L.len[b];
+    for (int k = 0; k < 2; ++k) {
+      const Group &Gr = L.grp[k];
+      if (Gr.n_heads == 0) continue;
+      const int64_t wgs_per_range = (int64_t)Gr.n_heads * (G / Gc);
+      const int64_t n_ct = ceil_div(occupied(ctx, Gr, n_past), ZZ_TILE_SLOTS);  // every occupied cached tile is read
+      for (int64_t iq0 = 0; iq0 < n_new; iq0 += QB) {
+        const int64_t iq_last = (iq0 + QB < n_new ? iq0 + QB : n_new) - 1;
+        const int64_t I_lo = n_past + iq0, k_hi = iq_last / ZZ_TILE_SLOTS;
+        // the causal lower triangle at this granularity: every cached position plus staged tiles up to the diagonal
+        const int64_t all = ceil_div(n_past, ZZ_TILE_SLOTS) + k_hi + 1;
+        int64_t ks_end = 0, kw_begin = 0;
+        if (Gr.streaming) {
+          if (n_past < S) {
+            const int64_t e = (S - 1 - n_past) / ZZ_TILE_SLOTS;
+            ks_end = (e < k_hi ? e : k_hi) + 1;
+          }
+          const int64_t first_win = I_lo - W + 1 - n_past;
+          kw_begin = first_win > 0 ? first_win / ZZ_TILE_SLOTS : 0;
+          if (kw_begin < ks_end) kw_begin = ks_end;
         }
-        const int64_t first_win = I_lo - W + 1 - n_past;
-        kw_begin = first_win > 0 ? first_win / ZZ_TILE_SLOTS : 0;
-        if (kw_begin < ks_end) kw_begin = ks_end;
+        const int64_t v = n_ct + ks_end + (k_hi >= kw_begin ? k_hi - kw_begin + 1 : 0);
+        vis += v * wgs_per_range;
+        cau += all * wgs_per_range;
       }
-      const int64_t v = n_ct + ks_end + (k_hi >= kw_begin ? k_hi - kw_begin + 1 : 0);
-      vis += v * wgs_per_range;
-      cau += all * wgs_per_range;
     }
   }
   *visited = vis;

@@ -59,6 +59,18 @@ struct zz_decode_params {
   float scale_log2e;              // softmax scale * log2(e)
 };
 
+// Decode over sequences of different lengths: the workgroups of all sequences form one
+// flat grid dimension, sequence b owning workgroups [first_wg[b], first_wg[b+1]); every
+// per-sequence quantity (occupied slots, slot of the newest token) follows from seq_len[b].
+// The fields of `u` that describe one common length (n_valid, n_tiles_valid, n_splits,
+// new_slot) are unused except new_slot's sign: >= 0 means the step appends.
+struct zz_decode_ragged_params {
+  zz_decode_params u;
+  int32_t sink, window;
+  uint32_t seq_len[ZZ_MAX_RAGGED_BATCH];        // tokens the attention of sequence b sees
+  uint16_t first_wg[ZZ_MAX_RAGGED_BATCH + 1];   // prefix sums of the per-sequence split counts
+};
+
 // Where the keys of a prefill call come from: cached tiles, then the staged chunk.
 struct zz_prefill_params {
   zz_group_dev grp;
@@ -82,6 +94,7 @@ struct zz_stage_params {
 
 hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s);
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
+hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s);
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s);
 hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s);

@@ -191,7 +191,8 @@ __device__ __forceinline__ bf16x8 softmax_step(const float (&x)[8], float &m, fl
 // attention is one launch.
 // --------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
+__device__ __forceinline__ void decode_body(const zz_decode_params &p, const int split, const int b, const int n_valid,
+                                            const int n_tiles_valid, const int n_splits, const int new_slot) {
   constexpr int KS = D / 32;      // MFMA k-steps over the head dimension
   constexpr int NL = D / 16;      // 1 KiB loads in the K part (= 2*KS) and in the V part
   constexpr int TILE_U4 = 8 * D;  // uint4 per KV tile
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kg = lane >> 4;
-  const int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  const int hg = blockIdx.y;
   const int G = p.group_size;
   const int g = p.heads[hg];
 
@@ -216,9 +217,9 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
 
   const uint4 *tiles = (const uint4 *)p.grp.base + ((int64_t)b * p.grp.n_heads + hg) * p.grp.n_tiles * TILE_U4 + lane;
   const int t0 = split * p.tiles_per_split;
-  const int t1 = min(t0 + p.tiles_per_split, p.n_tiles_valid);
-  const int last_tile = p.n_tiles_valid - 1;
-  const bool ragged = (p.n_valid & 31) != 0;
+  const int t1 = min(t0 + p.tiles_per_split, n_tiles_valid);
+  const int last_tile = n_tiles_valid - 1;
+  const bool partial_tail = (n_valid & 31) != 0;
 
   f32x4 acc[NL];
 #pragma unroll
@@ -237,8 +238,8 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
   // token's slot with the new rows, and stores the same pieces to the cache for the
   // steps to come; nobody else reads that slot in this launch, and what it held (the
   // token evicted from a ring, or nothing) is replaced in registers whatever the load saw.
-  const int tile_new = p.new_slot >> 5;  // new_slot < 0: nothing to append
-  const bool owner = p.new_slot >= 0 && tile_new >= t0 + wave && tile_new < t1 && ((tile_new - t0 - wave) & 3) == 0;
+  const int tile_new = new_slot >> 5;  // new_slot < 0: nothing to append
+  const bool owner = new_slot >= 0 && tile_new >= t0 + wave && tile_new < t1 && ((tile_new - t0 - wave) & 3) == 0;
   uint4 knew[KS];
   unsigned short vnew[NL];
   if (owner) {
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
     for (int i = 0; i < NL; ++i) vnew[i] = vp[16 * i];
   }
   auto patch_new_token = [&](uint4(&kv)[2 * NL]) __attribute__((always_inline)) {
-    const int tn = p.new_slot & 31, jn = tn & 15, kgn = jn >> 2;
+    const int tn = new_slot & 31, jn = tn & 15, kgn = jn >> 2;
     const int en = 4 * (tn >> 4) + (tn & 3);  // which of the lane's 8 V tokens
     uint4 *tile = const_cast<uint4 *>(tiles) - lane + (int64_t)tile_new * TILE_U4;
     // (value selects with constant register indices: a conditional store into kv[] would
@@ -293,20 +294,20 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
       x[r] = s0[r] * p.scale_log2e;
       x[4 + r] = s1[r] * p.scale_log2e;
     }
-    if (ragged && t == last_tile) {
+    if (partial_tail && t == last_tile) {
       // slots past n_valid were never written: no score, and their V bits (possibly
       // NaN patterns) must not reach the accumulating MFMA
       const int base = t * 32 + 4 * kg;
       unsigned int keep[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        if (base + r >= p.n_valid) x[r] = ZZ_NEG_INF;
-        if (base + 16 + r >= p.n_valid) x[4 + r] = ZZ_NEG_INF;
+        if (base + r >= n_valid) x[r] = ZZ_NEG_INF;
+        if (base + 16 + r >= n_valid) x[4 + r] = ZZ_NEG_INF;
       }
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const int s_lo = base + (w >= 2 ? 16 : 0) + 2 * (w & 1);
-        keep[w] = (s_lo < p.n_valid ? 0x0000ffffu : 0u) | (s_lo + 1 < p.n_valid ? 0xffff0000u : 0u);
+        keep[w] = (s_lo < n_valid ? 0x0000ffffu : 0u) | (s_lo + 1 < n_valid ? 0xffff0000u : 0u);
       }
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
       O += s_o[w][c][d] * f;
     }
     const int h = g * G + c;
-    if (p.n_splits == 1) {
+    if (n_splits == 1) {
       ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)(O / L);
     } else {
       const int64_t row = ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS + split;
@@ -384,7 +385,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
       }
     }
   }
-  if (p.n_splits == 1) return;
+  if (n_splits == 1) return;
 
   // ---- cross-split log-sum-exp combine by whichever workgroup of the unit ends last ----
   // The partial stores above are device-coherent; each wave waits until its own have
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
   __syncthreads();
   int *counter = p.counters + b * p.n_kv_heads + g;
   if (threadIdx.x == 0)
-    s_is_last = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.n_splits - 1);
+    s_is_last = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_splits - 1);
   __syncthreads();
   if (!s_is_last) return;
   // Three short phases instead of one thread walking all splits (each device-coherent
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
   float *s_ms = &s_o[0][0][0];                 // [16][ZZ_MAX_SPLITS] maxima, then weights
   float *s_ls = s_ms + 16 * ZZ_MAX_SPLITS;     // [16][ZZ_MAX_SPLITS] sums
   static_assert(sizeof(s_o) >= 2 * 16 * ZZ_MAX_SPLITS * sizeof(float), "merge scratch fits the reduction buffer");
-  const int ns = p.n_splits;
+  const int ns = n_splits;
   for (int idx = threadIdx.x; idx < G * ns; idx += 256) {
     const int c = idx / ns, s = idx - c * ns;
     const int64_t row = ((int64_t)b * p.n_q_heads + g * G + c) * ZZ_MAX_SPLITS + s;
@@ -451,6 +452,30 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
     ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)O;
   }
   if (threadIdx.x == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
+  decode_body<D>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
+}
+
+// Sequences of different lengths: grid (all workgroups of all sequences, heads of the group).
+// A workgroup finds its sequence in the prefix sums of the per-sequence split counts (a scan
+// over scalar kernel arguments) and derives that sequence's occupied slots and the slot of
+// its newest token from its length; the rest is the kernel above.
+template <int D>
+__global__ __launch_bounds__(256) void zz_decode_ragged_kernel(zz_decode_ragged_params p) {
+  const int wg = blockIdx.x;
+  int b = 0;
+  while (b + 1 < p.u.batch && p.first_wg[b + 1] <= wg) ++b;
+  const int split = wg - p.first_wg[b];
+  const int n_splits = p.first_wg[b + 1] - p.first_wg[b];
+  const int len = (int)p.seq_len[b];
+  const bool streaming = p.u.grp.streaming != 0;
+  const int n_valid = streaming ? min(len, p.sink + p.window) : len;
+  const int newest = len - 1;
+  const int slot = (!streaming || newest < p.sink) ? newest : p.sink + (newest - p.sink) % p.window;
+  decode_body<D>(p.u, split, b, n_valid, (n_valid + 31) >> 5, n_splits, p.u.new_slot >= 0 ? slot : -1);
 }
 
 // Zeroes the split counters once per context (the library never memsets caller memory).
@@ -1016,6 +1041,12 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
   hipError_t e = p.head_dim == 128 ? launch(zz_decode_kernel<128>, grid, dim3(256), s, p)
                                    : launch(zz_decode_kernel<64>, grid, dim3(256), s, p);
   return e;
+}
+
+hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s) {
+  const dim3 grid(total_wg, p.u.grp.n_heads, 1);
+  return p.u.head_dim == 128 ? launch(zz_decode_ragged_kernel<128>, grid, dim3(256), s, p)
+                             : launch(zz_decode_ragged_kernel<64>, grid, dim3(256), s, p);
 }
 
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s) {

@@ -224,6 +224,78 @@ def test_decode_plan_fills_the_chip_and_respects_limits():
     assert ns == 128 and tps == 32
 
 
+def test_per_sequence_lengths_and_their_error_paths():
+    cfg, keep = mk(B=3)
+    ctx = fake_ctx(cfg, keep)
+    h, L, A = ctx._h, zb.lib, 0x30000000
+    assert [ctx.seq_len(0, b) for b in range(3)] == [0, 0, 0]
+    ctx.set_seq_len(0, 1, 700)
+    assert [ctx.seq_len(0, b) for b in range(3)] == [0, 700, 0] and ctx.layer_len(0) == 700   # the longest
+    assert ctx.seq_len(1, 1) == 0                                           # other layers untouched
+    assert L.zz_attn_decode(h, 0, A, A, None) == E["ESTATE"]                # sequences 0 and 2 are empty
+    assert L.zz_seq_len(h, 0, 3) == E["ERANGE"] and L.zz_seq_len(h, 0, -1) == E["ERANGE"]
+    assert L.zz_seq_len(h, 2, 0) == E["ERANGE"] and L.zz_seq_len(None, 0, 0) == E["EINVAL"]
+    assert L.zz_set_seq_len(h, 0, 3, 1) == E["ERANGE"] and L.zz_set_seq_len(h, 0, 0, 1101) == E["ERANGE"]
+    assert L.zz_set_seq_len(h, 0, 0, -1) == E["ERANGE"]
+    for fn, args in ((L.zz_kv_append_seq, (A, A)), (L.zz_attn_prefill_seq, (A, A, A))):
+        tail = (A, None) if fn is L.zz_attn_prefill_seq else (None,)
+        assert fn(h, 0, 3, *args, 4, *tail) == E["ERANGE"]                  # no such sequence
+        assert fn(h, 0, -1, *args, 4, *tail) == E["ERANGE"]
+        assert fn(h, 2, 0, *args, 4, *tail) == E["ERANGE"]                  # no such layer
+        assert fn(h, 0, 0, *args, 0, *tail) == 0                            # n_new == 0: no-op
+        assert fn(h, 0, 0, *args, -1, *tail) == E["ERANGE"]
+        assert fn(h, 0, 1, *args, 401, *tail) == E["ENOSPC"]                # 700 + 401 > max_ctx
+        assert fn(None, 0, 0, *args, 4, *tail) == E["EINVAL"]
+    assert L.zz_kv_append_seq(h, 0, 0, None, A, 4, None) == E["EINVAL"]
+    assert L.zz_kv_append_seq(h, 0, 0, A + 2, A, 4, None) == E["EALIGN"]
+    assert L.zz_attn_prefill_seq(h, 0, 0, A, A, A, 1025, A, None) == E["ERANGE"]   # > max_chunk
+    assert L.zz_attn_prefill_seq(h, 0, 0, A, A, A, 4, None, None) == E["EINVAL"]
+    assert L.zz_attn_prefill_seq(h, 0, 0, A, A, A + 4, 4, A, None) == E["EALIGN"]
+    # batched calls are bounded by the longest sequence
+    assert L.zz_kv_append(h, 0, A, A, 401, None) == E["ENOSPC"]
+    assert L.zz_attn_prefill(h, 0, A, A, A, 401, A, None) == E["ENOSPC"]
+    ctx.set_seq_len(0, 1, 1100); ctx.set_seq_len(0, 0, 5); ctx.set_seq_len(0, 2, 5)
+    assert L.zz_decode_step(h, 0, A, A, A, A, None) == E["ENOSPC"]
+    assert [ctx.seq_len(0, b) for b in range(3)] == [5, 1100, 5]           # failed calls change no length
+    ctx.set_layer_len(0, 9)
+    assert [ctx.seq_len(0, b) for b in range(3)] == [9, 9, 9]
+    ctx.reset()
+    assert [ctx.seq_len(0, b) for b in range(3)] == [0, 0, 0]
+    # more sequences than the per-sequence decode launch can describe
+    cfg2, keep2 = mk(B=zb.ZZ_MAX_RAGGED_BATCH + 1)
+    ctx2 = fake_ctx(cfg2, keep2)
+    ctx2.set_layer_len(0, 10); ctx2.set_seq_len(0, 0, 11)
+    assert L.zz_attn_decode(ctx2._h, 0, A, A, None) == E["EUNSUPPORTED"]
+
+
+@pytest.mark.parametrize("lens", [(131072, 65536, 32768, 16384), (131072, 131071, 100, 7), (5000, 4000, 3000, 2000),
+                                  (40, 40, 41, 40), (131072, 1, 1, 1)])
+def test_decode_plan_for_unequal_lengths_fits_one_round_and_balances(lens):
+    w = zz_inputs.WORKLOADS["c3_llama8b_128k_b4"]
+    lm = zz_inputs.draw_layer_mask(0, 32, 16)
+    cfg, keep = zb.make_config(32, 32, 8, 128, 4, w.context, 64, 256, 0, zb.ZZ_ZIGZAG, 0.0, lm, None)
+    ctx = fake_ctx(cfg, keep)
+    ctx.tune(zb.TUNE_NUM_CU, 256)
+    r = int(np.flatnonzero(lm == 0)[0]); s = int(np.flatnonzero(lm == 1)[0])
+    for b, n in enumerate(lens):
+        ctx.set_seq_len(r, b, n); ctx.set_seq_len(s, b, n)
+    ns_max, tps = ctx.decode_plan(r, 0)
+    tiles = [-(-n // 32) for n in lens]
+    splits = [-(-t // tps) for t in tiles]
+    assert ns_max == max(splits) <= zb.ZZ_MAX_SPLITS
+    assert sum(splits) * 8 <= 256                                # all workgroups of the launch resident at once
+    assert tps >= 16 or tps >= max(tiles)                        # short caches are not split
+    if tps > 16:                                                 # tps is minimal: one tile less per split no longer fits
+        assert sum(-(-t // (tps - 1)) for t in tiles) * 8 > 256
+    assert tps <= max(16, 2 * -(-sum(tiles) // 32))              # within 2x of the perfectly even share
+    ns_s, tps_s = ctx.decode_plan(s, 1)                          # streaming layer: every cache is at most 10 tiles
+    assert ns_s == 1 and tps_s >= max(min(t, 10) for t in tiles)
+    assert ctx.decode_plan(r, 1) == (0, 0)
+    ctx.tune(zb.TUNE_DECODE_SPLITS, 8)
+    ns_max, tps = ctx.decode_plan(r, 0)
+    assert ns_max == -(-max(tiles) // tps) <= 8
+
+
 def needed_tiles_bruteforce(n_past, n_new, streaming, S, W, QB):
     """Per workgroup (QB consecutive queries): 32-key tiles holding at least one key some
     query of the block may see (oracle predicates), cached tiles by slot, staged tiles by
@@ -265,7 +337,13 @@ def test_prefill_tile_counts_cover_every_needed_tile_and_skip_the_rest(n_past, n
             assert visited - need * wgs <= wgs * n_blocks * (-(-(S + W) // 32))
             if n_past >= 1000:
                 assert visited < 0.5 * causal                # sink + window: most of the triangle is skipped
-    assert ctx.prefill_tile_counts(0, 513)[0] if False else True
+    # unequal lengths: the counts are the sum over the sequences, each with its own past
+    for layer, streaming in ((0, False), (1, True)):
+        ctx.set_seq_len(layer, 0, n_past); ctx.set_seq_len(layer, 1, n_past + 77)
+        visited, causal = ctx.prefill_tile_counts(layer, n_new)
+        per_seq = [needed_tiles_bruteforce(n, n_new, streaming, S, W, QB) for n in (n_past, n_past + 77)]
+        assert causal == sum(c for _, c in per_seq) * (wgs // B)
+        assert sum(n for n, _ in per_seq) * (wgs // B) <= visited <= causal
     h = ctx._h
     a, b_ = ctypes.c_int64(), ctypes.c_int64()
     assert zb.lib.zz_prefill_tile_counts(h, 0, 513, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
