@@ -13,7 +13,7 @@ attention launch.  Prints ONE JSON line:
                    same step in the comparison layout / at the other context length / with
                    the append as its own launch / without the append / replayed from a HIP graph
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|sweep]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|sweep|unequal]
 """
 from __future__ import annotations
 
@@ -423,6 +423,9 @@ def main():
     if wname == "sweep":
         from bench_sweep import bench_sweep
         out = bench_sweep(args)
+    elif wname == "unequal":
+        from bench_unequal import bench_unequal
+        out = bench_unequal(args, DecodeRun, HBM_PEAK_GBPS)
     elif wname == "c4_prefill_64k":
         from bench_prefill import bench_prefill
         out = bench_prefill(args, wname)

@@ -352,7 +352,7 @@ def test_decode_full_size_128k_batch4_sampled_units():
     G = Hq // Hkv
     st = H.Stack(2, Hq, Hkv, D, B, N, w.sink, w.window, layer_is_streaming=[0, 1])
     gen = torch.Generator(device="cuda").manual_seed(1234)
-    sample = [(0, 0), (0, 5), (B - 1, Hkv - 1), (2, 3)]
+    sample = [(0, 0), (0, 5), (B - 1, Hkv - 1), (2, 3), (1, 2)]
     kept = {u: ([], []) for u in sample}
     chunk = 8192
     for a in range(0, N, chunk):
@@ -374,6 +374,22 @@ def test_decode_full_size_128k_batch4_sampled_units():
             V = np.concatenate(kept[(b, g)][1])[J]
             want = O.decode_unit(qh[b, g * G:(g + 1) * G], K, V, scale)
             check(got[b, g * G:(g + 1) * G], want, ("128k", layer, b, g))
+        assert np.isfinite(got).all()
+    # The same caches read as sequences of different lengths, in one launch per layer (the
+    # configuration `bench.py --workload unequal` times).  A retrieval cache of n tokens is
+    # the first n slots of the longer one; a full streaming cache holds S + W tokens whatever
+    # the length, and decode attends all of them, so its outputs must not change.
+    lens = [N, N // 2, N // 4 + 5, N // 8]
+    for layer, streaming in ((0, False), (1, True)):
+        for b, n in enumerate(lens):
+            st.ctx.set_seq_len(layer, b, n)
+        got = H.from_dev(st.decode(layer, q))
+        for (b, g) in sample:
+            J = O.attended_positions(N - 1, True, w.sink, w.window) if streaming else np.arange(lens[b])
+            K = np.concatenate(kept[(b, g)][0])[J]
+            V = np.concatenate(kept[(b, g)][1])[J]
+            want = O.decode_unit(qh[b, g * G:(g + 1) * G], K, V, scale)
+            check(got[b, g * G:(g + 1) * G], want, ("128k, unequal lengths", layer, b, g))
         assert np.isfinite(got).all()
 
 
