@@ -343,16 +343,18 @@ def test_tiny_stack_prefill_then_decode(seed):
 # full size, in the launch configuration the benchmark times: sampled units
 # ---------------------------------------------------------------------------
 
-def test_decode_full_size_128k_batch4_sampled_units():
-    """One retrieval and one streaming layer of the 128k / batch-4 workload, filled
-    through zz_kv_append; the oracle recomputes sampled (batch, kv head) units."""
+@pytest.mark.parametrize("wname", ["c3_llama8b_128k_b4", "c2_llama8b_32k_b1", "c5_mha7b_32k_b8"])
+def test_decode_full_size_sampled_units(wname):
+    """One retrieval and one streaming layer of each decode workload at its full size (128k /
+    batch 4; 32k / batch 1; 32k / batch 8 with 32 KV heads), filled through zz_kv_append, in the
+    launch configuration the benchmark times; the oracle recomputes sampled (batch, kv head) units."""
     H, zb = _harness()
-    w = zz_inputs.WORKLOADS["c3_llama8b_128k_b4"]
+    w = zz_inputs.WORKLOADS[wname]
     B, Hq, Hkv, D, N = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.context
     G = Hq // Hkv
     st = H.Stack(2, Hq, Hkv, D, B, N, w.sink, w.window, layer_is_streaming=[0, 1])
     gen = torch.Generator(device="cuda").manual_seed(1234)
-    sample = [(0, 0), (0, 5), (B - 1, Hkv - 1), (2, 3), (1, 2)]
+    sample = sorted({(0, 0), (0, 5), (B - 1, Hkv - 1), (B // 2, 3), (min(1, B - 1), 2)})
     kept = {u: ([], []) for u in sample}
     chunk = 8192
     for a in range(0, N, chunk):
@@ -373,13 +375,15 @@ def test_decode_full_size_128k_batch4_sampled_units():
             K = np.concatenate(kept[(b, g)][0])[J]
             V = np.concatenate(kept[(b, g)][1])[J]
             want = O.decode_unit(qh[b, g * G:(g + 1) * G], K, V, scale)
-            check(got[b, g * G:(g + 1) * G], want, ("128k", layer, b, g))
+            check(got[b, g * G:(g + 1) * G], want, (wname, layer, b, g))
         assert np.isfinite(got).all()
+    if B < 4:
+        return
     # The same caches read as sequences of different lengths, in one launch per layer (the
     # configuration `bench.py --workload unequal` times).  A retrieval cache of n tokens is
     # the first n slots of the longer one; a full streaming cache holds S + W tokens whatever
     # the length, and decode attends all of them, so its outputs must not change.
-    lens = [N, N // 2, N // 4 + 5, N // 8]
+    lens = ([N, N // 2, N // 4 + 5, N // 8] * B)[:B]
     for layer, streaming in ((0, False), (1, True)):
         for b, n in enumerate(lens):
             st.ctx.set_seq_len(layer, b, n)
@@ -389,7 +393,7 @@ def test_decode_full_size_128k_batch4_sampled_units():
             K = np.concatenate(kept[(b, g)][0])[J]
             V = np.concatenate(kept[(b, g)][1])[J]
             want = O.decode_unit(qh[b, g * G:(g + 1) * G], K, V, scale)
-            check(got[b, g * G:(g + 1) * G], want, ("128k, unequal lengths", layer, b, g))
+            check(got[b, g * G:(g + 1) * G], want, (wname, "unequal lengths", layer, b, g))
         assert np.isfinite(got).all()
 
 
