@@ -190,13 +190,15 @@ __device__ __forceinline__ bf16x8 softmax_step(const float (&x)[8], float &m, fl
 // workgroup of a unit that finishes last merges the unit's partials, so a layer's
 // attention is one launch.
 // --------------------------------------------------------------------------
-template <int D>
+template <int D, int WAVES>
 __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int split, const int b, const int n_valid,
                                             const int n_tiles_valid, const int n_splits, const int new_slot) {
   constexpr int KS = D / 32;      // MFMA k-steps over the head dimension
   constexpr int NL = D / 16;      // 1 KiB loads in the K part (= 2*KS) and in the V part
   constexpr int TILE_U4 = 8 * D;  // uint4 per KV tile
   constexpr int OP = D + 4;       // padded row of the cross-wave reduction buffer
+  constexpr int NT = 64 * WAVES;  // threads per workgroup
+  constexpr int COLS = WAVES == 4 ? 16 : 8;  // columns the reduction buffer holds (group size limit of the launch)
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, kg = lane >> 4;
@@ -239,7 +241,7 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
   // steps to come; nobody else reads that slot in this launch, and what it held (the
   // token evicted from a ring, or nothing) is replaced in registers whatever the load saw.
   const int tile_new = new_slot >> 5;  // new_slot < 0: nothing to append
-  const bool owner = new_slot >= 0 && tile_new >= t0 + wave && tile_new < t1 && ((tile_new - t0 - wave) & 3) == 0;
+  const bool owner = new_slot >= 0 && tile_new >= t0 + wave && tile_new < t1 && ((tile_new - t0 - wave) & (WAVES - 1)) == 0;
   uint4 knew[KS];
   unsigned short vnew[NL];
   if (owner) {
@@ -328,25 +330,33 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
       acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kv[NL + i]), P, acc[i], 0, 0, 0);
   };
 
-  {
+  if constexpr (WAVES == 8) {
+    // at most two tiles per wave (the launcher guarantees t1 - t0 <= 16): both requested at once
+    uint4 bufA[2 * NL], bufB[2 * NL];
+    const int ta = t0 + wave, tb = ta + WAVES;
+    if (ta < t1) load_tile(bufA, ta);
+    if (tb < t1) load_tile(bufB, tb);
+    if (ta < t1) compute(bufA, ta);
+    if (tb < t1) compute(bufB, tb);
+  } else {
     uint4 bufA[2 * NL], bufB[2 * NL];
     int t = t0 + wave;
     if (t < t1) load_tile(bufA, t);
-    for (; t < t1; t += 2 * ZZ_WAVES_PER_WG) {
-      const int tn = t + ZZ_WAVES_PER_WG;
+    for (; t < t1; t += 2 * WAVES) {
+      const int tn = t + WAVES;
       if (tn < t1) load_tile(bufB, tn);
       compute(bufA, t);
       if (tn < t1) {
-        if (tn + ZZ_WAVES_PER_WG < t1) load_tile(bufA, tn + ZZ_WAVES_PER_WG);
+        if (tn + WAVES < t1) load_tile(bufA, tn + WAVES);
         compute(bufB, tn);
       }
     }
   }
 
   // ---- combine the four waves of the workgroup through LDS ----
-  __shared__ float s_o[ZZ_WAVES_PER_WG][16][OP];
-  __shared__ float s_m[ZZ_WAVES_PER_WG][16];
-  __shared__ float s_l[ZZ_WAVES_PER_WG][16];
+  __shared__ float s_o[WAVES][COLS][OP];
+  __shared__ float s_m[WAVES][COLS];
+  __shared__ float s_l[WAVES][COLS];
   float l_tot = l + xor_lanes(l, 16);
   l_tot += xor_lanes(l_tot, 32);
   if (col < G) {
@@ -360,15 +370,15 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * D; idx += NT) {
     const int c = idx / D, d = idx % D;
     float M = ZZ_NEG_INF;
 #pragma unroll
-    for (int w = 0; w < ZZ_WAVES_PER_WG; ++w) M = fmaxf(M, s_m[w][c]);
+    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w][c]);
     const float Ms = (M == ZZ_NEG_INF) ? 0.f : M;
     float L = 0.f, O = 0.f;
 #pragma unroll
-    for (int w = 0; w < ZZ_WAVES_PER_WG; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
       const float f = fast_exp2(s_m[w][c] - Ms);
       L += s_l[w][c] * f;
       O += s_o[w][c][d] * f;
@@ -406,18 +416,18 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
   // per thread; (2) one wave per column turns them into normalised weights 2^(m_s-M)/L
   // with lane-parallel reductions; (3) each output element is a weighted sum of its
   // partials, loads issued eight at a time.  The cross-wave buffer is free by now.
-  float *s_ms = &s_o[0][0][0];                 // [16][ZZ_MAX_SPLITS] maxima, then weights
-  float *s_ls = s_ms + 16 * ZZ_MAX_SPLITS;     // [16][ZZ_MAX_SPLITS] sums
-  static_assert(sizeof(s_o) >= 2 * 16 * ZZ_MAX_SPLITS * sizeof(float), "merge scratch fits the reduction buffer");
+  float *s_ms = &s_o[0][0][0];                   // [COLS][ZZ_MAX_SPLITS] maxima, then weights
+  float *s_ls = s_ms + COLS * ZZ_MAX_SPLITS;     // [COLS][ZZ_MAX_SPLITS] sums
+  static_assert(sizeof(s_o) >= 2 * COLS * ZZ_MAX_SPLITS * sizeof(float), "merge scratch fits the reduction buffer");
   const int ns = n_splits;
-  for (int idx = threadIdx.x; idx < G * ns; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * ns; idx += NT) {
     const int c = idx / ns, s = idx - c * ns;
     const int64_t row = ((int64_t)b * p.n_q_heads + g * G + c) * ZZ_MAX_SPLITS + s;
     s_ms[c * ZZ_MAX_SPLITS + s] = load_device_coherent(p.part_ml + row * 2);
     s_ls[c * ZZ_MAX_SPLITS + s] = load_device_coherent(p.part_ml + row * 2 + 1);
   }
   __syncthreads();
-  for (int c = wave; c < G; c += ZZ_WAVES_PER_WG) {
+  for (int c = wave; c < G; c += WAVES) {
     float m0 = lane < ns ? s_ms[c * ZZ_MAX_SPLITS + lane] : ZZ_NEG_INF;
     float m1 = lane + 64 < ns ? s_ms[c * ZZ_MAX_SPLITS + lane + 64] : ZZ_NEG_INF;
     float M = fmaxf(m0, m1);
@@ -434,7 +444,7 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
     if (lane + 64 < ns) s_ms[c * ZZ_MAX_SPLITS + lane + 64] = f1 * inv;
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+  for (int idx = threadIdx.x; idx < G * D; idx += NT) {
     const int c = idx / D, d = idx % D;
     const int h = g * G + c;
     const float *po = p.part_o + ((int64_t)b * p.n_q_heads + h) * ZZ_MAX_SPLITS * D + d;
@@ -456,15 +466,24 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
 
 template <int D>
 __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
-  decode_body<D>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
+  decode_body<D, 4>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
+}
+
+// Short caches (one workgroup per unit, at most 16 tiles: a streaming head's sink + window):
+// eight waves, so that every wave has at most two tiles and requests both at once.  The launch
+// is a chain of latencies (dispatch, one memory round trip, two tiles of arithmetic, the merge
+// through LDS) instead of two or three round trips in a row.  Group sizes up to 8.
+template <int D>
+__global__ __launch_bounds__(512) void zz_decode_short_kernel(zz_decode_params p) {
+  decode_body<D, 8>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
 }
 
 // Sequences of different lengths: grid (all workgroups of all sequences, heads of the group).
 // A workgroup finds its sequence in the prefix sums of the per-sequence split counts (a scan
 // over scalar kernel arguments) and derives that sequence's occupied slots and the slot of
 // its newest token from its length; the rest is the kernel above.
-template <int D>
-__global__ __launch_bounds__(256) void zz_decode_ragged_kernel(zz_decode_ragged_params p) {
+template <int D, int WAVES>
+__device__ __forceinline__ void decode_ragged_body(const zz_decode_ragged_params &p) {
   const int wg = blockIdx.x;
   int b = 0;
   while (b + 1 < p.u.batch && p.first_wg[b + 1] <= wg) ++b;
@@ -475,7 +494,17 @@ __global__ __launch_bounds__(256) void zz_decode_ragged_kernel(zz_decode_ragged_
   const int n_valid = streaming ? min(len, p.sink + p.window) : len;
   const int newest = len - 1;
   const int slot = (!streaming || newest < p.sink) ? newest : p.sink + (newest - p.sink) % p.window;
-  decode_body<D>(p.u, split, b, n_valid, (n_valid + 31) >> 5, n_splits, p.u.new_slot >= 0 ? slot : -1);
+  decode_body<D, WAVES>(p.u, split, b, n_valid, (n_valid + 31) >> 5, n_splits, p.u.new_slot >= 0 ? slot : -1);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void zz_decode_ragged_kernel(zz_decode_ragged_params p) {
+  decode_ragged_body<D, 4>(p);
+}
+// every sequence's cache is short (one workgroup each, at most 16 tiles): eight waves, as above
+template <int D>
+__global__ __launch_bounds__(512) void zz_decode_ragged_short_kernel(zz_decode_ragged_params p) {
+  decode_ragged_body<D, 8>(p);
 }
 
 // Zeroes the split counters once per context (the library never memsets caller memory).
@@ -1038,6 +1067,9 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
 
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
   const dim3 grid(p.n_splits, p.grp.n_heads, p.batch);
+  if (p.n_splits == 1 && p.n_tiles_valid > 4 && p.n_tiles_valid <= 16 && p.group_size <= 8)
+    return p.head_dim == 128 ? launch(zz_decode_short_kernel<128>, grid, dim3(512), s, p)
+                             : launch(zz_decode_short_kernel<64>, grid, dim3(512), s, p);
   hipError_t e = p.head_dim == 128 ? launch(zz_decode_kernel<128>, grid, dim3(256), s, p)
                                    : launch(zz_decode_kernel<64>, grid, dim3(256), s, p);
   return e;
@@ -1045,6 +1077,13 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
 
 hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s) {
   const dim3 grid(total_wg, p.u.grp.n_heads, 1);
+  int64_t longest = 0;
+  for (int b = 0; b < p.u.batch; ++b) longest = p.seq_len[b] > longest ? p.seq_len[b] : longest;
+  if (p.u.grp.streaming && longest > p.sink + p.window) longest = p.sink + p.window;
+  const int64_t most_tiles = (longest + ZZ_TILE_SLOTS - 1) / ZZ_TILE_SLOTS;
+  if (total_wg == p.u.batch && most_tiles > 4 && most_tiles <= 16 && p.u.group_size <= 8)
+    return p.u.head_dim == 128 ? launch(zz_decode_ragged_short_kernel<128>, grid, dim3(512), s, p)
+                               : launch(zz_decode_ragged_short_kernel<64>, grid, dim3(512), s, p);
   return p.u.head_dim == 128 ? launch(zz_decode_ragged_kernel<128>, grid, dim3(256), s, p)
                              : launch(zz_decode_ragged_kernel<64>, grid, dim3(256), s, p);
 }
