@@ -124,7 +124,9 @@ def bench_prefill(args, wname):
         pairs_sample = sum(len(O.attended_positions(c * C + r, bool(lmask[l]), w.sink, w.window))
                            for (c, l) in keep_out for r in rows) * len(heads)
         total_pairs = flop / (4 * D)
-        cpu = dict(value=total_pairs / pairs_sample * t_cpu * 1e3 / (T * B), unit="ms/token", cores=1, kind="oracle",
+        t_cpu_prompt = total_pairs / pairs_sample * t_cpu     # seconds the oracle would need for the whole prompt
+        cpu = dict(value=flop / t_cpu_prompt / 1e12, unit="TFLOP/s", ms_per_prompt_token=t_cpu_prompt * 1e3 / (T * B),
+                   cores=1, kind="oracle", measured_on_sample_s=t_cpu, extrapolated=True,
                    sample=f"{n_rows} (query row, head) pairs of the last chunk of one retrieval and one streaming "
                           f"layer, {t_cpu:.2f} s single-threaded, extrapolated by attended (query,key) pairs")
     return {
@@ -141,7 +143,7 @@ def bench_prefill(args, wname):
         "tile": "32 keys x 64 query positions x 2 heads (one workgroup's share of a KV tile)",
         # every visited (workgroup, tile) pair is computed in full: scores and P V for 64 x 2 x 32 pairs
         "tile_granular_flop_per_step": vis * 64 * 2 * 32 * 4 * D,
-        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128,4,3>, retrieval layer, last 4096-token chunk of 65536",
+        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128, 2>, retrieval layer, last 4096-token chunk of 65536 (chunk staging included)",
                      "achieved": flop_last / t_kernel / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_last / t_kernel / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop_per_launch": flop_last,
                      "avg_launch_us": t_kernel * 1e6, "traffic": None},
