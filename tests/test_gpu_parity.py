@@ -203,6 +203,17 @@ def test_decode_group_sizes(Hq, Hkv):
     run_decode_case(2, Hq, Hkv, 64, 8, 40, 700, 32, True, one_by_one_tail=33)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(16, 2), (6, 2), (32, 2), (8, 8)])
+@pytest.mark.parametrize("S,W", [(32, 100), (256, 256), (256, 288)])
+def test_decode_short_caches_around_the_eight_wave_kernel_limits(Hq, Hkv, S, W):
+    """Unsplit caches of 5 to 16 tiles and group sizes up to 8 run with eight waves per workgroup
+    (one or two tiles per wave); 17 tiles, or a group of 16, fall back to four waves.  Ring caches of
+    5 (last one partial), 16 and 17 tiles, and retrieval caches of the same sizes, D = 128 and 64."""
+    for D in (128, 64):
+        run_decode_case(2, Hq, Hkv, D, S, W, 1000, 90 + D, True, one_by_one_tail=3)
+        run_decode_case(1, Hq, Hkv, D, S, W, S + W - 1, 91 + D, False, splits=1)
+
+
 def test_decode_peaked_softmax_rescales_running_max():
     for streaming in (False, True):
         run_decode_case(1, 8, 2, 128, 64, 256, 2500, 55, streaming, q_gain=8.0)
