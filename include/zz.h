@@ -26,8 +26,10 @@
  *     only enqueue kernels: the library never allocates device memory, never
  *     synchronises and never copies the arena.
  *   - Return value: 0 (ZZ_OK) or a negative ZZ_E* code.  All argument checks run on
- *     the host before anything is launched; a call that fails has launched nothing
- *     and changed no length.  n_new == 0 is a successful no-op.
+ *     the host before anything is launched; a call that fails one has launched nothing
+ *     and changed no length.  ZZ_EHIP (the runtime refused a launch) changes no length
+ *     either, but a call made of several launches (two head kinds, one launch per
+ *     sequence) does not recall those already issued.  n_new == 0 is a successful no-op.
  *   - Every sequence of the batch has its own length per layer.  The batched calls
  *     advance all B sequences by the same number of tokens, each from its own length;
  *     the *_seq calls advance one sequence, which is how prompts of different lengths
