@@ -521,14 +521,16 @@ __global__ void zz_zero_kernel(int *p, int n) {
 //
 // K/V tiles travel HBM/L2 -> LDS once per workgroup with direct-to-LDS loads
 // (global_load_lds_dwordx4: each wave deposits 1 KiB chunks, lane L at byte L*16,
-// i.e. the operand image unchanged) into two rings of three half-tiles (K parts,
+// i.e. the operand image unchanged) into two rings of four half-tiles (K parts,
 // V parts); every wave reads operands back with conflict-free ds_read_b128.
 //
-// The loop is software-pipelined over three tiles so that, with one wave per SIMD,
-// the matrix pipe and the vector ALU work at the same time:
+// The loop is software-pipelined over three tiles, so that the three stages of an
+// iteration are independent of each other:
 //     iteration n:   S(n+1) = K(n+1) Q^T        (MFMA)
-//                    P(n)   = softmax step on S(n)   (VALU, independent of the above)
 //                    O     += V(n-1)^T P(n-1)   (MFMA)
+//                    P(n)   = softmax step on S(n)   (VALU)
+// Two workgroups are resident per compute unit, i.e. two waves per SIMD: while one runs
+// its block of MFMAs the other runs its softmax on the vector ALU.
 // The running reference maximum is only raised when a column's scores exceed it by
 // more than 2^8 (exact in fp32/bf16, P stays <= 256), so the accumulators are
 // rescaled a handful of times per query, not whenever a new maximum appears.
