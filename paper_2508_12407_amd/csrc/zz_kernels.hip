@@ -575,14 +575,20 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Maximum over the four key groups of a column: lanes L, L^16, L^32, L^48.
+// v_permlane16_swap exchanges the odd 16-lane rows of its first register with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second;
+// started from two copies of a value, each step leaves every lane with its own value in one
+// register and its partner's in the other.  Written as asm: through the builtin this compiler
+// reads both results from the first register, so the maximum of the pair degenerates to a
+// broadcast of key group 0.  (s_nop: the compiler does not insert the wait states a VALU write
+// needs before a lane-permuting read inside an asm statement.)
 __device__ __forceinline__ float max_over_kg(float v) {
-  // lanes L, L^16, L^32, L^48 hold the four key groups of one column
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const float m1 = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
-  const unsigned w = __builtin_bit_cast(unsigned, m1);
-  auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\tv_max_f32 %0, %0, %1" : "+v"(a), "+v"(b));
+  b = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_max_f32 %0, %0, %1" : "+v"(a), "+v"(b));
+  return a;
 }
 
 #define ZZ_RESCALE_THRESHOLD 8.0f  // in log2 units

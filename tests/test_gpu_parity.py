@@ -310,6 +310,40 @@ def test_prefill_peaked_softmax():
         run_prefill_case(1, 8, 2, 128, 16, 64, 600, [0, 300, 600], 23, streaming, q_gain=8.0)
 
 
+@pytest.mark.parametrize("W", [1, 7, 40, 100])
+def test_prefill_streaming_without_sink_tokens(W):
+    """S = 0: nothing but the window.  A query's first visible tile may then show keys to some of
+    the four key-group lanes of its column only, and columns next to it may see nothing at all yet."""
+    run_prefill_case(2, 4, 1, 128, 0, W, 201, [0, 99, 145, 176, 201], 61, True)
+    run_prefill_case(1, 16, 2, 64, 0, W, 137, [0, 137], 62, True)
+    run_decode_case(2, 8, 2, 128, 0, W, 150, 63, True, one_by_one_tail=5)
+
+
+def test_prefill_reference_maximum_is_the_maximum_over_all_key_groups():
+    """Keys whose slot falls in key group 0 of a tile score 2^-196 of the others' 2^+196 (log2
+    units): a reference maximum taken from one key group instead of the whole column is off by
+    2^392 and overflows; the true maximum gives the mean of V over the high-scoring keys."""
+    H, zb = _harness()
+    D, T = 64, 200
+    q = np.zeros((1, T, 1, D), np.float32)
+    k = np.zeros((1, T, 1, D), np.float32)
+    _, _, v = zz_inputs.make_qkv(77, 1, T, 1, 1, D)
+    q[..., 0] = 32.0
+    for j in range(T):
+        k[0, j, 0, 0] = -34.0 if (j % 16) // 4 == 0 else 34.0      # score * scale * log2(e) = -+196
+    for streaming, S, W in ((False, 0, 1), (True, 0, 50), (True, 3, 20)):
+        st = H.Stack(1, 1, 1, D, 1, T + 1, S, W, max_chunk=T, layer_is_streaming=[int(streaming)], poison_arena=True)
+        qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+        got = H.from_dev(st.prefill(0, qd[:, :150].contiguous(), kd[:, :150].contiguous(), vd[:, :150].contiguous()))
+        want = O.attention(q, k, v, kinds_of(streaming, 1), S, W)
+        check(got, want[:, :150], ("prefill", streaming, S, W))
+        st.append(0, kd[:, :150].contiguous(), vd[:, :150].contiguous())
+        got = H.from_dev(st.prefill(0, qd[:, 150:].contiguous(), kd[:, 150:].contiguous(), vd[:, 150:].contiguous()))
+        check(got, want[:, 150:], ("prefill, second chunk", streaming, S, W))
+        st.append(0, kd[:, 150:].contiguous(), vd[:, 150:].contiguous())
+        check(H.from_dev(st.decode(0, qd[:, T - 1].contiguous())), want[:, T - 1], ("decode", streaming, S, W))
+
+
 def test_prefill_mixed_layout_equals_zigzag_where_masks_coincide():
     """Section 3.2: the method leaves prefilling unchanged; a mixed layer whose heads
     are all one kind must give what the zigzag layer of that kind gives."""
