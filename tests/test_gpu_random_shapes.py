@@ -96,3 +96,142 @@ def test_random_configuration(seed):
             slots = np.flatnonzero(valid)
             for b in sorted({0, B - 1}):
                 assert np.array_equal(st.read_cache_rows(arena, 0, which, b, g, slots), img[b, g, slots]), (c, g, which, b)
+
+
+def draw_decode_case(seed):
+    r = np.random.default_rng(7000 + seed)
+    D = int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    G = int(r.choice([1, 2, 4, 8, 16]))
+    if Hkv * G > 32:
+        G = 32 // Hkv
+    B = int(r.integers(1, 6))
+    S = int(r.choice([0, 1, 16, 64]))
+    W = int(r.choice([1, 32, 256, 500]))
+    longest = int(r.choice([40, 600, 3000, 6000]))
+    if r.random() < 0.35:
+        lens = [int(r.integers(1, longest + 1))] * B                 # one common length: the single-length launch
+    else:
+        lens = [int(r.integers(1, longest + 1)) for _ in range(B)]   # one launch over unequal lengths
+    layout = str(r.choice(["retrieval", "streaming", "mixed"]))
+    mask = (r.random(Hkv) < 0.5).astype(np.uint8)
+    splits = [None, None, 1, 2, 5, 37, 128][int(r.integers(0, 7))]
+    cus = [None, None, 8, 64, 1024][int(r.integers(0, 5))]
+    return dict(D=D, Hkv=Hkv, Hq=Hkv * G, B=B, S=S, W=W, lens=lens, layout=layout, mask=mask, splits=splits, cus=cus)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_decode_configuration(seed):
+    """Caches of random (equal or unequal) lengths up to 6000 tokens, random split counts and
+    compute-unit counts for the split plan; two fused steps and one append + attention."""
+    H, zb = _harness()
+    c = draw_decode_case(seed)
+    D, Hkv, Hq, B, S, W = c["D"], c["Hkv"], c["Hq"], c["B"], c["S"], c["W"]
+    G = Hq // Hkv
+    lens = list(c["lens"])
+    total = max(lens) + 3
+    _, k, v = zz_inputs.make_qkv(9000 + seed, B, total, 1, Hkv, D)        # K, V of every sequence
+    qs = zz_inputs.make_qkv(9500 + seed, B, 3, Hq, Hkv, D)[0]             # the three queries of every sequence
+    if c["layout"] == "mixed":
+        st = H.Stack(1, Hq, Hkv, D, B, total, S, W, layout=zb.ZZ_MIXED, kvhead_is_streaming=c["mask"][None, :],
+                     poison_arena=True)
+        kinds = c["mask"].astype(bool)
+    else:
+        st = H.Stack(1, Hq, Hkv, D, B, total, S, W, layer_is_streaming=[int(c["layout"] == "streaming")],
+                     poison_arena=True)
+        kinds = np.full(Hkv, c["layout"] == "streaming")
+    st.workspace.fill_(0xFF)
+    if c["splits"] is not None:
+        st.ctx.tune(zb.TUNE_DECODE_SPLITS, c["splits"])
+    if c["cus"] is not None:
+        st.ctx.tune(zb.TUNE_NUM_CU, c["cus"])
+    kd, vd, qd = H.to_dev_bf16(k), H.to_dev_bf16(v), H.to_dev_bf16(qs)
+    sp = st.stream_ptr()
+    for b, n in enumerate(lens):
+        st.ctx.kv_append_seq(0, b, kd[b:b + 1, :n].contiguous(), vd[b:b + 1, :n].contiguous(), n, sp)
+    scale = O.default_scale(D)
+
+    def want_now():
+        out = np.zeros((B, Hq, D))
+        for b, n in enumerate(lens):
+            for g in range(Hkv):
+                J = O.attended_positions(n - 1, bool(kinds[g]), S, W)
+                out[b, g * G:(g + 1) * G] = O.decode_unit(qs[b, step, g * G:(g + 1) * G], k[b, J, g], v[b, J, g], scale)
+        return out
+
+    for step in range(3):
+        newk = torch.stack([kd[b, n] for b, n in enumerate(lens)])[:, None].contiguous()
+        newv = torch.stack([vd[b, n] for b, n in enumerate(lens)])[:, None].contiguous()
+        if step < 2:
+            out = st.decode_step(0, qd[:, step].contiguous(), newk, newv)
+        else:
+            st.ctx.kv_append(0, newk, newv, 1, sp)
+            out = st.decode(0, qd[:, step].contiguous())
+        lens = [n + 1 for n in lens]
+        check(H.from_dev(out), want_now(), ("decode", step, {k_: v_ for k_, v_ in c.items() if k_ != "mask"}))
+        assert [st.ctx.seq_len(0, b) for b in range(B)] == lens
+    arena = st.arena_host()
+    b, g = B - 1, Hkv - 1
+    cap = O.cache_capacity(bool(kinds[g]), S, W, total)
+    for which, X in ((0, k), (1, v)):
+        img, valid = O.expected_cache(zz_inputs.bf16_bits(X[b:b + 1]), lens[b], bool(kinds[g]), S, W, cap)
+        slots = np.flatnonzero(valid)
+        assert np.array_equal(st.read_cache_rows(arena, 0, which, b, g, slots), img[0, g, slots]), (c, which)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_unequal_prompts(seed):
+    """Prompts of random lengths entering a batch one sequence at a time in random chunks
+    (zz_attn_prefill_seq / zz_kv_append_seq), then a batched chunk and a fused decode step on the
+    unequal lengths; every sequence against the oracle on its own."""
+    H, zb = _harness()
+    r = np.random.default_rng(11000 + seed)
+    D = int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 4]))
+    G = int(r.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    B = int(r.integers(2, 5))
+    S = int(r.choice([0, 4, 16, 64]))
+    W = int(r.choice([1, 32, 100, 256]))
+    lens = [int(r.integers(0, 400)) for _ in range(B)]
+    n_batched = int(r.integers(1, 50))
+    layout = str(r.choice(["retrieval", "streaming", "mixed"]))
+    mask = (r.random(Hkv) < 0.5).astype(np.uint8)
+    total = max(lens) + n_batched + 1
+    q, k, v = zz_inputs.make_qkv(12000 + seed, B, total, Hq, Hkv, D)
+    kw = dict(layout=zb.ZZ_MIXED, kvhead_is_streaming=mask[None, :]) if layout == "mixed" else \
+        dict(layer_is_streaming=[int(layout == "streaming")])
+    st = H.Stack(1, Hq, Hkv, D, B, total, S, W, max_chunk=max(max(lens), n_batched, 1), poison_arena=True, **kw)
+    kinds = mask.astype(bool) if layout == "mixed" else np.full(Hkv, layout == "streaming")
+    st.workspace.fill_(0xFF)
+    qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+    sp = st.stream_ptr()
+    what = dict(D=D, Hq=Hq, Hkv=Hkv, B=B, S=S, W=W, lens=lens, n_batched=n_batched, layout=layout)
+
+    def want_rows(b, a, e):
+        return O.attention(q[b:b + 1, :e], k[b:b + 1, :e], v[b:b + 1, :e], kinds, S, W, rows=list(range(a, e)))
+
+    for b, n in enumerate(lens):
+        cuts = sorted(set([0, n] + [int(x) for x in r.integers(0, n + 1, size=int(r.integers(0, 4)))]))
+        for a, e in zip(cuts[:-1], cuts[1:]):
+            qa, ka, va = qd[b:b + 1, a:e].contiguous(), kd[b:b + 1, a:e].contiguous(), vd[b:b + 1, a:e].contiguous()
+            out = torch.empty_like(qa)
+            st.ctx.attn_prefill_seq(0, b, qa, ka, va, e - a, out, sp)
+            check(H.from_dev(out), want_rows(b, a, e), ("prefill_seq", b, a, e, what))
+            st.ctx.kv_append_seq(0, b, ka, va, e - a, sp)
+    assert [st.ctx.seq_len(0, b) for b in range(B)] == lens
+    qa = torch.stack([qd[b, n:n + n_batched] for b, n in enumerate(lens)]).contiguous()
+    ka = torch.stack([kd[b, n:n + n_batched] for b, n in enumerate(lens)]).contiguous()
+    va = torch.stack([vd[b, n:n + n_batched] for b, n in enumerate(lens)]).contiguous()
+    got = H.from_dev(st.prefill(0, qa, ka, va))
+    for b, n in enumerate(lens):
+        check(got[b:b + 1], want_rows(b, n, n + n_batched), ("batched prefill", b, what))
+    st.append(0, ka, va)
+    lens = [n + n_batched for n in lens]
+    out = st.decode_step(0, torch.stack([qd[b, n] for b, n in enumerate(lens)]).contiguous(),
+                         torch.stack([kd[b, n] for b, n in enumerate(lens)])[:, None].contiguous(),
+                         torch.stack([vd[b, n] for b, n in enumerate(lens)])[:, None].contiguous())
+    got = H.from_dev(out)
+    for b, n in enumerate(lens):
+        check(got[b:b + 1], want_rows(b, n, n + 1)[:, 0], ("decode_step", b, what))
+    assert [st.ctx.seq_len(0, b) for b in range(B)] == [n + 1 for n in lens]
