@@ -8,6 +8,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libzz.so")
+CLIENT_PATH = os.path.join(PKG_DIR, "zz_c_abi_client")   # the torch-free client of the C ABI (tests/c_abi_client.cpp)
 SOURCES = [os.path.join(CSRC, "zz_api.cpp"), os.path.join(CSRC, "zz_transport.cpp"), os.path.join(CSRC, "zz_kernels.hip")]
 
 
@@ -32,7 +33,23 @@ def build(verbose: bool = False) -> str:
         print("\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed building libzz.so")
+    build_c_client(verbose)
     return LIB_PATH
+
+
+def build_c_client(verbose: bool = False) -> str:
+    """Host-only program that drives libzz.so through include/zz.h with plain hipMalloc memory."""
+    cmd = [hipcc(), "-O2", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi_client.cpp"), "-L" + PKG_DIR, "-lzz", "-Wl,-rpath,$ORIGIN",
+           "-o", CLIENT_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(" ".join(cmd))
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building the C ABI client")
+    return CLIENT_PATH
 
 
 if __name__ == "__main__":
