@@ -169,3 +169,44 @@ def test_unequal_lengths_that_become_equal_take_the_single_length_path_again():
         out = st.decode_step(0, qd[:, 41].contiguous(), kd[:, 41:42].contiguous(), vd[:, 41:42].contiguous())
         check(H.from_dev(out), O.decode_row(q[:, 41], k[:, :42], v[:, :42], 41, kinds, S, W), ("equal again", kind))
         check_caches(H, st, [42, 42], k, v, kinds, S, W, T)
+
+
+def test_largest_batch_of_unequal_lengths_and_a_larger_batch_of_equal_ones():
+    """256 sequences of different lengths in one decode launch (the most the launch can describe),
+    and 300 sequences of one length (no such limit); a sample of sequences against the oracle."""
+    H, zb = _harness()
+    Hq, Hkv, D, S, W = 4, 2, 64, 8, 40
+    for B, unequal in ((zb.ZZ_MAX_RAGGED_BATCH, True), (300, False)):
+        rng = np.random.default_rng(B)
+        lens = [int(x) for x in rng.integers(1, 400, size=B)] if unequal else [123] * B
+        T = max(lens) + 2
+        q, k, v = zz_inputs.make_qkv(81, B, T, Hq, Hkv, D)
+        for kind in ("retrieval", "streaming"):
+            st, kinds = make_stack(H, zb, kind, Hq, Hkv, D, B, T, S, W, 0)
+            qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+            sp = st.stream_ptr()
+            if unequal:
+                # the whole batch appended once to the longest length, then the lengths declared:
+                # a retrieval cache's prefix is the shorter cache; a ring is rebuilt per sequence below
+                if kind == "retrieval":
+                    st.append(0, kd[:, :T - 2].contiguous(), vd[:, :T - 2].contiguous())
+                    for b, n in enumerate(lens):
+                        st.ctx.set_seq_len(0, b, n)
+                else:
+                    for b, n in enumerate(lens):
+                        st.ctx.kv_append_seq(0, b, kd[b:b + 1, :n].contiguous(), vd[b:b + 1, :n].contiguous(), n, sp)
+            else:
+                st.append(0, kd[:, :123].contiguous(), vd[:, :123].contiguous())
+            cur = list(lens)
+            for step in range(2):
+                out = st.decode_step(0, torch.stack([qd[b, n] for b, n in enumerate(cur)]).contiguous(),
+                                     torch.stack([kd[b, n] for b, n in enumerate(cur)])[:, None].contiguous(),
+                                     torch.stack([vd[b, n] for b, n in enumerate(cur)])[:, None].contiguous())
+                cur = [n + 1 for n in cur]
+                got = H.from_dev(out)
+                assert np.isfinite(got).all()
+                for b in (0, 1, B // 2, B - 2, B - 1):
+                    n = cur[b]
+                    want = O.decode_row(q[b:b + 1, n - 1], k[b:b + 1, :n], v[b:b + 1, :n], n - 1, kinds, S, W)
+                    check(got[b:b + 1], want, ("large batch", B, kind, step, b))
+            assert [st.ctx.seq_len(0, b) for b in (0, B - 1)] == [cur[0], cur[-1]]
