@@ -609,7 +609,9 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   const int b = blockIdx.z;
   const int g = p.heads[hg];
   const int QW = 16 * (NB / Gc);
-  const int iq_wg = blockIdx.x * ZZ_WAVES_PER_WG * QW;  // first query index of the workgroup
+  // later query blocks see more staged keys: they are dispatched first, so the launch does not end
+  // on its longest workgroups
+  const int iq_wg = (gridDim.x - 1 - blockIdx.x) * ZZ_WAVES_PER_WG * QW;  // first query index of the workgroup
   const int iq0 = iq_wg + wave * QW;                    // ... of the wave (may lie past n_new: an idle wave
                                                         // computes on masked columns and stores nothing)
   const int i_lo = p.n_past + iq0;                      // the wave's first query position
