@@ -51,13 +51,36 @@ def draw_case(seed):
                 q_gain=q_gain)
 
 
+def draw_long_case(seed):
+    """As draw_case, but one sequence of 600 to 3000 tokens: several query blocks, many cached tiles."""
+    c = draw_case(seed)
+    r = np.random.default_rng(50000 + seed)
+    c["B"] = 1
+    c["Hkv"] = int(r.choice([1, 2]))
+    c["Hq"] = c["Hkv"] * int(r.choice([1, 2, 4]))
+    c["mask"] = (r.random(c["Hkv"]) < 0.5).astype(np.uint8)
+    c["T"] = int(r.integers(600, 3000))
+    n_cuts = int(r.integers(0, 5))
+    c["cuts"] = sorted(set([0, c["T"]] + [int(x) for x in r.integers(1, c["T"] + 1, size=n_cuts)]))
+    c["W"] = int(r.choice([1, 7, 32, 100, 256, 700]))
+    return c
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_configuration_longer_contexts(seed):
+    run_configuration(draw_long_case(seed), 6000 + seed)
+
+
 @pytest.mark.parametrize("seed", range(36))
 def test_random_configuration(seed):
+    run_configuration(draw_case(seed), 5000 + seed)
+
+
+def run_configuration(c, data_seed):
     H, zb = _harness()
-    c = draw_case(seed)
     D, Hkv, Hq, B, S, W, T, steps = c["D"], c["Hkv"], c["Hq"], c["B"], c["S"], c["W"], c["T"], c["steps"]
     total = T + 2 * steps
-    q, k, v = zz_inputs.make_qkv(5000 + seed, B, total, Hq, Hkv, D, q_gain=c["q_gain"])
+    q, k, v = zz_inputs.make_qkv(data_seed, B, total, Hq, Hkv, D, q_gain=c["q_gain"])
     max_chunk = max(b - a for a, b in zip(c["cuts"][:-1], c["cuts"][1:]))
     if c["layout"] == "mixed":
         st = H.Stack(1, Hq, Hkv, D, B, total, S, W, max_chunk=max_chunk, layout=zb.ZZ_MIXED,
