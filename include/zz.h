@@ -38,6 +38,15 @@
  *     sequence, zz_attn_decode and zz_decode_step stay at one launch per head kind
  *     (batches of at most ZZ_MAX_RAGGED_BATCH sequences, else ZZ_EUNSUPPORTED).
  *   - A context must not be used from two host threads at once.
+ *   - HIP-graph capture.  Every call may be made on a stream that is being captured: the
+ *     launches are recorded instead of run.  The host-side bookkeeping (sequence lengths)
+ *     advances once, at the call; a replay repeats the recorded kernels with the recorded
+ *     arguments (the same slot is written again, the same number of tokens is attended) and
+ *     changes no length.  To decode further tokens by replay, the caller captures one graph per
+ *     step or re-records.  The split counters in the workspace are cleared by a small kernel
+ *     ahead of the attention launch of every zz_attn_decode / zz_decode_step call until one such
+ *     call has been made on a stream that was not being captured; that clear, when recorded,
+ *     stays in the graph and is harmless on replay (counters are zero between launches).
  */
 #ifndef ZZ_H
 #define ZZ_H
@@ -85,12 +94,21 @@ typedef struct zz_config {
   const uint8_t *kvhead_is_streaming; /* HOST [n_layers*n_kv_heads]; required for ZZ_MIXED */
 } zz_config;
 
-/* Bytes of device memory the caller must provide.  0 if the config is invalid. */
+/* Bytes of DEVICE memory the caller must provide; 0 if the config is invalid.  Pure host
+ * arithmetic.  The arena holds the KV cache of every layer: max_ctx slots per retrieval head
+ * (Section 1: the cache grows linearly with the context) and S + W slots per streaming head
+ * (Sections 1 and 3.3: the rest is waived), in whole 32-slot tiles; layout under
+ * zz_kv_elem_offset.  The workspace holds the split-K partials and counters of one decode
+ * launch and the staged chunk of one prefill call (build conventions, not from the paper). */
 size_t zz_arena_bytes(const zz_config *cfg);
 size_t zz_workspace_bytes(const zz_config *cfg);
 
-/* Validate `cfg`, lay the per-layer caches out inside `kv_arena` (256-byte aligned)
- * and create a context with every layer empty.  The arena is not touched. */
+/* Validate `cfg`, lay the per-layer caches out inside `kv_arena` (256-byte aligned DEVICE
+ * memory) and create a context (HOST memory, freed by zz_destroy) with every layer empty.
+ * The per-layer kind comes from layer_is_streaming (Section 2.2: p of the L layers stream)
+ * or, for the comparison layout, from kvhead_is_streaming (Section 2.1).  Neither the arena
+ * nor the workspace is touched.  ZZ_ENOSPC if either is smaller than zz_*_bytes says,
+ * ZZ_EALIGN if misaligned, ZZ_ESTATE if the mask of the chosen layout is NULL. */
 int zz_create(const zz_config *cfg, void *kv_arena, size_t arena_bytes, void *workspace,
               size_t workspace_bytes, zz_ctx **out);
 int zz_destroy(zz_ctx *ctx);
@@ -138,7 +156,9 @@ int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, con
                    void *stream);
 
 /* Tokens appended to the layer so far (of its longest sequence, if they differ), or a
- * negative error code. */
+ * negative error code.  Host bookkeeping only (build convention): a streaming layer counts
+ * every token it has seen, not the S + W it still holds, because the slot of the next token
+ * and the positions of the cached ones follow from that count. */
 int64_t zz_layer_len(const zz_ctx *ctx, int layer);
 /* Overwrite the length of every sequence of a layer (restoring a snapshot of the arena).
  * 0 <= len <= max_ctx. */
@@ -152,7 +172,10 @@ int zz_set_seq_len(zz_ctx *ctx, int layer, int b, int64_t len);
 int zz_layer_launches(const zz_ctx *ctx, int layer);
 
 /* Pure host arithmetic: the cache slot a token at position `pos` of (layer, kv_head)
- * is written to.  Retrieval: pos.  Streaming: pos if pos < S, else S + (pos - S) mod W.
+ * is written to.  Retrieval: pos.  Streaming, with S the sink size and W the window length of
+ * Section 3.3: pos if pos < S, else S + (pos - S) mod W.  The paper only names the two
+ * parameters; that sink tokens sit in S fixed slots outside the ring and that the ring has
+ * exactly W slots (the window includes the query's own position) is this build's reading.
  * Negative error code on bad arguments (ZZ_ERANGE if pos >= max_ctx on a retrieval head). */
 int64_t zz_slot_of(const zz_config *cfg, int layer, int kv_head, int64_t pos);
 
@@ -172,26 +195,11 @@ int64_t zz_slot_of(const zz_config *cfg, int layer, int kv_head, int64_t pos);
  * (element index * 2 = byte offset inside the tile). */
 int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv_head, int64_t slot, int d);
 
-/* Tuning knobs, for measurement.  key: */
-enum {
-  ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 1)  */
-  ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
-  ZZ_TUNE_NUM_CU = 3             /* override the detected compute-unit count               */
-};
-int zz_tune(zz_ctx *ctx, int key, int value);
-
-/* Split count and tiles per split the next zz_attn_decode would use for group
- * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty.
- * With unequal sequence lengths one tiles-per-split value serves the whole launch,
- * sequence b takes ceil(its tiles / tiles_per_split) workgroups per head, and *n_splits
- * is the largest of those counts. */
-int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
-
 /* Pure host arithmetic: how many (workgroup, 32-key tile) visits the next
  * zz_attn_prefill(layer, n_new) performs, and how many a kernel that skipped
  * nothing below the causal diagonal would perform at the same granularity
- * (a workgroup covers 64, 128 or 256 consecutive query positions for group sizes
- * that are multiples of 4, of 2, or odd).  1 - visited/causal is the skipped-tile
+ * (a workgroup covers 64 consecutive query positions for even group sizes and 128 for odd
+ * ones).  1 - visited/causal is the skipped-tile
  * fraction that the sink + window mask of streaming heads allows (Section 3.3). */
 int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *visited, int64_t *causal);
 
@@ -210,17 +218,39 @@ int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *vis
 int zz_transport_select(const float *alpha, int n_layers, int n_heads, float sparsity, float omega,
                         uint8_t *layer_is_streaming, double *loss);
 
+const char *zz_strerror(int code);
+/* What the HIP runtime reported for the calling thread's most recent ZZ_EHIP
+ * (which kernel, hipGetErrorString text); "" if there was none. */
+const char *zz_last_error_detail(void);
+
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement and tuning.  Nothing below is part of the method or needed to use it: these
+ * calls exist for the benchmark and the tests (forcing split counts, reading the launch plan,
+ * timing the memory system).
+ * ------------------------------------------------------------------------------------------ */
+
+/* Tuning knobs, for measurement.  key: */
+enum {
+  ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 1)  */
+  ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
+  ZZ_TUNE_NUM_CU = 3             /* override the detected compute-unit count               */
+};
+int zz_tune(zz_ctx *ctx, int key, int value);
+
+/* Split count and tiles per split the next zz_attn_decode would use for group
+ * `group` (0 retrieval, 1 streaming) of the layer; 0 splits if the group is empty.
+ * With unequal sequence lengths one tiles-per-split value serves the whole launch,
+ * sequence b takes ceil(its tiles / tiles_per_split) workgroups per head, and *n_splits
+ * is the largest of those counts. */
+int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
+
 /* Measurement aid, not part of the method: streams `bytes` (rounded down to 16 KiB) of DEVICE
  * memory `buf` through one workgroup per compute unit with the decode kernel's access pattern
  * and discards them; nontemporal != 0 uses the same non-temporal loads as the decode kernel.
  * Timed by the caller, it gives the read bandwidth the memory system delivers to that
  * pattern: the practical ceiling beside the published peak. */
 int zz_probe_read(zz_ctx *ctx, const void *buf, size_t bytes, int nontemporal, void *stream);
-
-const char *zz_strerror(int code);
-/* What the HIP runtime reported for the calling thread's most recent ZZ_EHIP
- * (which kernel, hipGetErrorString text); "" if there was none. */
-const char *zz_last_error_detail(void);
 
 #ifdef __cplusplus
 }

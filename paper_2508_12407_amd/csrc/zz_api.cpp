@@ -131,7 +131,12 @@ struct zz_ctx {
   // them the latency every workgroup pays for its first tile and for its merge.
   int tune_wg_per_cu = 1;
   int tune_splits = 0;
-  bool counters_zeroed = false;  // split counters are cleared by the first decode call
+  // The split counters live in caller memory that the library has never seen: every decode call
+  // enqueues a small clear ahead of its attention launch until one such clear has been issued on
+  // a stream that is not being captured (a clear recorded into a graph only runs when the graph
+  // is replayed, so it does not count).  The merge re-arms a counter it has used.
+  bool counters_zeroed = false;
+  std::vector<int64_t> seen, tiles;  // per-sequence scratch of the decode call (sized at create: no heap work per call)
 };
 
 namespace {
@@ -210,10 +215,9 @@ void plan_decode(const zz_ctx *ctx, int cu, const Group &G, int64_t len, int *n_
 // stragglers: tps is the smallest value whose workgroups fit in one round (if the batch
 // allows it at all), which also equalises the work per workgroup as far as whole tiles can.
 // Returns the workgroups per head; first_wg[0..B] are the prefix sums.
-int plan_decode_ragged(const zz_ctx *ctx, int cu, const Group &G, const std::vector<int64_t> &len, uint16_t *first_wg,
+int plan_decode_ragged(const zz_ctx *ctx, int cu, const Group &G, const int64_t *len, int64_t *tiles, uint16_t *first_wg,
                        int *tiles_per_split) {
-  const int B = (int)len.size();
-  std::vector<int64_t> tiles(B);
+  const int B = ctx->cfg.batch;
   int64_t total = 0, longest = 0;
   for (int b = 0; b < B; ++b) {
     tiles[b] = ceil_div(occupied(ctx, G, len[b]), ZZ_TILE_SLOTS);
@@ -295,6 +299,8 @@ int zz_create(const zz_config *cfg, void *kv_arena, size_t arena_bytes, void *wo
   ctx->arena = (char *)kv_arena;
   ctx->ws = (char *)workspace;
   ctx->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  ctx->seen.assign(cfg->batch, 0);
+  ctx->tiles.assign(cfg->batch, 0);
   *out = ctx;
   return ZZ_OK;
 }
@@ -410,7 +416,8 @@ int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *
   if (L.grp[group].n_heads == 0) return ZZ_OK;
   if (ctx->cfg.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
   uint16_t first_wg[ZZ_MAX_RAGGED_BATCH + 1];
-  plan_decode_ragged(ctx, cu, L.grp[group], L.len, first_wg, tiles_per_split);
+  std::vector<int64_t> tiles(ctx->cfg.batch);
+  plan_decode_ragged(ctx, cu, L.grp[group], L.len.data(), tiles.data(), first_wg, tiles_per_split);
   for (int b = 0; b < ctx->cfg.batch; ++b)
     if (first_wg[b + 1] - first_wg[b] > *n_splits) *n_splits = first_wg[b + 1] - first_wg[b];
   return ZZ_OK;
@@ -545,60 +552,77 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
   if (misaligned(q, 16) || misaligned(out, 16) || misaligned(k_new, 16) || misaligned(v_new, 16)) return ZZ_EALIGN;
   Layer &L = ctx->lo.layers[layer];
   const zz_config &c = ctx->cfg;
-  if (fused && L.longest() + 1 > c.max_ctx) return ZZ_ENOSPC;
-  std::vector<int64_t> seen(L.len);  // tokens the attention of each sequence sees
-  for (auto &v : seen) {
-    v += fused ? 1 : 0;
-    if (v <= 0) return ZZ_ESTATE;
+  const int64_t add = fused ? 1 : 0;
+  // one pass over the lengths: equal or not, longest, shortest
+  const int64_t len0 = L.len[0];
+  int64_t longest = len0, shortest = len0;
+  for (int b = 1; b < c.batch; ++b) {
+    const int64_t v = L.len[b];
+    longest = v > longest ? v : longest;
+    shortest = v < shortest ? v : shortest;
   }
-  const bool uniform = L.uniform();
+  const bool uniform = longest == shortest;
+  if (fused && longest + 1 > c.max_ctx) return ZZ_ENOSPC;
+  if (shortest + add <= 0) return ZZ_ESTATE;
   if (!uniform && c.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
   const int cu = num_cu(ctx);
   int *counters = (int *)(ctx->ws + ctx->lo.ws_counters);
   if (!ctx->counters_zeroed) {
+    const bool capturing = zz_stream_is_capturing((hipStream_t)stream);
     if (hipError_t e = zz_launch_zero(counters, c.batch * c.n_kv_heads, (hipStream_t)stream))
       return hip_failed("counter clear kernel", e);
-    ctx->counters_zeroed = true;
+    ctx->counters_zeroed = !capturing;
   }
   for (int k = 0; k < 2; ++k) {
     const Group &G = L.grp[k];
     if (G.n_heads == 0) continue;
-    zz_decode_ragged_params rp;
-    std::memset(&rp, 0, sizeof(rp));
-    zz_decode_params &p = rp.u;
-    p.grp = dev_group(ctx, G);
-    std::memcpy(p.heads, G.heads, sizeof(p.heads));
-    p.q = q;
-    p.out = out;
-    p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
-    p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
-    p.counters = counters;
-    p.k_new = k_new;
-    p.v_new = v_new;
-    p.batch = c.batch;
-    p.n_q_heads = c.n_q_heads;
-    p.n_kv_heads = c.n_kv_heads;
-    p.head_dim = c.head_dim;
-    p.group_size = c.n_q_heads / c.n_kv_heads;
-    p.scale_log2e = ctx->scale * 1.4426950408889634f;
+    // everything both launch forms share; the per-sequence form embeds it
+    auto fill = [&](zz_decode_params &p) {
+      p.grp = dev_group(ctx, G);
+      std::memcpy(p.heads, G.heads, sizeof(p.heads));
+      p.q = q;
+      p.out = out;
+      p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
+      p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
+      p.counters = counters;
+      p.k_new = k_new;
+      p.v_new = v_new;
+      p.batch = c.batch;
+      p.n_q_heads = c.n_q_heads;
+      p.n_kv_heads = c.n_kv_heads;
+      p.head_dim = c.head_dim;
+      p.group_size = c.n_q_heads / c.n_kv_heads;
+      p.scale_log2e = ctx->scale * 1.4426950408889634f;
+    };
     if (uniform) {
-      const int64_t len = seen[0];
+      zz_decode_params p;
+      fill(p);
+      const int64_t len = len0 + add;
       p.new_slot = fused ? (int32_t)slot_rule(G.streaming, len - 1, c.sink, c.window) : -1;
       p.n_valid = (int)occupied(ctx, G, len);
       p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
       plan_decode(ctx, cu, G, len, &p.n_splits, &p.tiles_per_split);
       if (hipError_t e = zz_launch_decode(p, (hipStream_t)stream)) return hip_failed("decode kernel", e);
     } else {
+      zz_decode_ragged_params rp;
+      fill(rp.u);
+      zz_decode_params &p = rp.u;
       p.new_slot = fused ? 0 : -1;  // only the sign is read: each sequence's slot follows from its length
+      p.n_valid = p.n_tiles_valid = p.n_splits = 0;
       rp.sink = c.sink;
       rp.window = c.window;
-      for (int b = 0; b < c.batch; ++b) rp.seq_len[b] = (uint32_t)seen[b];
-      const int total_wg = plan_decode_ragged(ctx, cu, G, seen, rp.first_wg, &p.tiles_per_split);
+      for (int b = 0; b < c.batch; ++b) {
+        ctx->seen[b] = L.len[b] + add;
+        rp.seq_len[b] = (uint32_t)ctx->seen[b];
+      }
+      const int total_wg =
+          plan_decode_ragged(ctx, cu, G, ctx->seen.data(), ctx->tiles.data(), rp.first_wg, &p.tiles_per_split);
       if (hipError_t e = zz_launch_decode_ragged(rp, total_wg, (hipStream_t)stream))
         return hip_failed("decode kernel (per-sequence lengths)", e);
     }
   }
-  L.len = seen;
+  if (fused)
+    for (auto &v : L.len) v += 1;
   return ZZ_OK;
 }
 

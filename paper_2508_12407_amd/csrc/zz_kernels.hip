@@ -1038,6 +1038,15 @@ int zz_query_num_cu() {
   return n;
 }
 
+bool zz_stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st != hipStreamCaptureStatusNone;
+}
+
 hipError_t zz_launch_append(const zz_append_params &p0, hipStream_t s) {
   zz_append_params p = p0;
   // many tokens into never-evicting heads: the tile-wise kernel; streaming heads (at most S+W

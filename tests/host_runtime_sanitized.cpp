@@ -4,6 +4,7 @@
 // the host hands to a launch (grid within limits, every sequence's split range inside the
 // partials the workspace holds, prefix sums consistent with the grid).  Built and run by
 // tests/test_host_sanitized.py.
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -24,6 +25,8 @@ static int g_launches = 0, g_fail = 0;
 // ---- recorders standing in for the launchers of zz_kernels.hip ----
 const char *hipGetErrorString(hipError_t) { return "stub"; }
 int zz_query_num_cu() { return 256; }
+static bool g_capturing = false;
+bool zz_stream_is_capturing(hipStream_t) { return g_capturing; }
 
 hipError_t zz_launch_append(const zz_append_params &p, hipStream_t) {
   ++g_launches;
@@ -69,8 +72,10 @@ hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_w
   }
   return hipSuccess;
 }
+static int g_zero_launches = 0;
 hipError_t zz_launch_zero(int *, int n, hipStream_t) {
   ++g_launches;
+  ++g_zero_launches;
   EXPECT(n > 0);
   return hipSuccess;
 }
@@ -98,7 +103,34 @@ static zz_ctx *make(int L, int Hq, int Hkv, int D, int B, int max_ctx, int S, in
 static unsigned rng_state = 12345;
 static unsigned rnd() { return rng_state = rng_state * 1664525u + 1013904223u; }
 
-int main() {
+// Host time of one zz_decode_step call (argument checks, launch plan, argument block), with the
+// recorders in place of the launches: what the library itself adds to a decode step per layer.
+static int time_decode_calls() {
+  void *T = (void *)0x30000000;
+  struct Case { const char *name; int B; bool unequal; } cases[] = {
+      {"batch 1, 32k, equal lengths", 1, false}, {"batch 4, 128k, equal lengths", 4, false},
+      {"batch 8, unequal lengths", 8, true}, {"batch 256, unequal lengths", 256, true}};
+  for (const Case &cs : cases) {
+    zz_ctx *ctx = make(2, 32, 8, 128, cs.B, 131072 + 8, 64, 256, 0, ZZ_ZIGZAG, {0, 1}, {});
+    const int reps = 200000;
+    double ns[2] = {0, 0};
+    for (int layer = 0; layer < 2; ++layer) {
+      const auto t0 = std::chrono::steady_clock::now();
+      for (int r = 0; r < reps; ++r) {
+        if ((r & 7) == 0)   // stay inside max_ctx; amortised over eight calls
+          for (int b = 0; b < cs.B; ++b) zz_set_seq_len(ctx, layer, b, cs.unequal ? 1000 + 500 * (b % 200) : (cs.B == 1 ? 32767 : 131071));
+        if (zz_decode_step(ctx, layer, T, T, T, T, nullptr) != ZZ_OK) return 1;
+      }
+      ns[layer] = std::chrono::duration<double, std::nano>(std::chrono::steady_clock::now() - t0).count() / reps;
+    }
+    std::printf("zz_decode_step host time, %s: retrieval layer %.0f ns, streaming layer %.0f ns per call\n", cs.name, ns[0], ns[1]);
+    zz_destroy(ctx);
+  }
+  return 0;
+}
+
+int main(int argc, char **argv) {
+  if (argc > 1 && std::strcmp(argv[1], "--time") == 0) return time_decode_calls();
   void *T = (void *)0x30000000;  // fake, aligned tensor address: the recorders never touch it
   // 1. zigzag stack, equal lengths: append / prefill / decode at many lengths and split settings
   {
@@ -120,6 +152,26 @@ int main() {
           EXPECT(zz_set_layer_len(ctx, layer, n) == ZZ_OK);
           EXPECT(zz_prefill_tile_counts(ctx, layer, n_new, &v, &c) == ZZ_OK && v > 0 && v <= c);
         }
+    EXPECT(zz_destroy(ctx) == ZZ_OK);
+  }
+  // 1b. the split counters are cleared ahead of every decode call until one clear has been issued
+  //     outside a stream capture (a clear recorded into a graph runs only on replay)
+  {
+    zz_ctx *ctx = make(1, 32, 8, 128, 1, 4096, 64, 256, 0, ZZ_ZIGZAG, {0}, {});
+    EXPECT(zz_set_layer_len(ctx, 0, 1000) == ZZ_OK);
+    g_zero_launches = 0;
+    g_capturing = true;
+    EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+    EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+    EXPECT(g_zero_launches == 2);
+    g_capturing = false;
+    EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+    EXPECT(g_zero_launches == 3);
+    EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+    g_capturing = true;
+    EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+    EXPECT(g_zero_launches == 3);
+    g_capturing = false;
     EXPECT(zz_destroy(ctx) == ZZ_OK);
   }
   // 2. unequal lengths, random, zigzag and mixed, up to the largest batch

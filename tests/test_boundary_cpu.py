@@ -352,6 +352,20 @@ def test_prefill_tile_counts_cover_every_needed_tile_and_skip_the_rest(n_past, n
     assert zb.lib.zz_prefill_tile_counts(h, 5, 8, ctypes.byref(a), ctypes.byref(b_)) == E["ERANGE"]
 
 
+@pytest.mark.parametrize("Hq,QB", [(8, 64), (4, 64), (6, 128), (2, 128)])
+def test_prefill_tile_counts_use_the_query_block_the_header_states(Hq, QB):
+    """zz.h: a workgroup covers 64 consecutive query positions for even group sizes, 128 for odd ones."""
+    Hkv, B, n_past, n_new = 2, 1, 500, 512
+    cfg, keep = zb.make_config(1, Hq, Hkv, 64, B, 8192, 16, 64, 512, zb.ZZ_ZIGZAG, 0.0, np.array([0], np.uint8), None)
+    ctx = fake_ctx(cfg, keep)
+    ctx.set_layer_len(0, n_past)
+    visited, causal = ctx.prefill_tile_counts(0, n_new)
+    G = Hq // Hkv
+    wgs = B * Hkv * (G // 2 if G % 2 == 0 else G)       # two heads of a group per workgroup, or one
+    want = sum(-(-n_past // 32) + (min(q0 + QB, n_new) - 1) // 32 + 1 for q0 in range(0, n_new, QB)) * wgs
+    assert visited == causal == want
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

@@ -529,6 +529,35 @@ def test_decode_step_captured_in_a_hip_graph_replays_identically(lengths):
         assert torch.equal(out, eager), rep
 
 
+def test_first_decode_of_a_context_recorded_into_a_graph_then_eager_then_replayed():
+    """The split counters sit in caller memory the library has never cleared.  When the very first
+    decode call of a context is recorded into a HIP graph, the clear it enqueues runs only on
+    replay: an eager call made before any replay must clear them itself.  Workspace filled with
+    a non-zero pattern; capture, eager, replay, eager - each against the oracle row."""
+    H, zb = _harness()
+    B, Hq, Hkv, D, S, W, T = 2, 8, 2, 128, 16, 64, 3000
+    q, k, v = zz_inputs.make_qkv(77, B, T, Hq, Hkv, D)
+    st = H.Stack(1, Hq, Hkv, D, B, T, S, W, layer_is_streaming=[0], poison_arena=True)
+    st.workspace.fill_(0x5A)
+    st.append(0, H.to_dev_bf16(k), H.to_dev_bf16(v))
+    assert st.ctx.decode_plan(0, 0)[0] > 1          # the launch really merges across workgroups
+    qd = H.to_dev_bf16(q[:, T - 1])
+    out = torch.zeros_like(qd)
+    want = O.decode_row(q[:, T - 1], k, v, T - 1, kinds_of(False, Hkv), S, W)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        st.ctx.attn_decode(0, qd, out, st.stream_ptr())
+    for what in ("eager before any replay", "replay", "eager", "replay"):
+        out.zero_()
+        if what.startswith("eager"):
+            st.ctx.attn_decode(0, qd, out, st.stream_ptr())
+        else:
+            g.replay()
+        torch.cuda.synchronize()
+        check(H.from_dev(out), want, what)
+
+
 def test_uniform_keys_give_the_mean_over_exactly_the_attended_set_on_gpu():
     """Closed form on the GPU path itself (no oracle involved): with K = 0 every visible key
     gets the same weight, so the output is the mean of V over the attended set.  V encodes
