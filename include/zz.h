@@ -62,6 +62,11 @@ extern "C" {
 #define ZZ_MAX_KV_HEADS 64 /* upper bound on n_kv_heads                                  */
 #define ZZ_MAX_SPLITS 128  /* upper bound on split-K partials per (batch, query head)    */
 #define ZZ_MAX_RAGGED_BATCH 256 /* largest batch whose sequences may differ in length at decode */
+/* Static split-K scratch of zz_attn_decode_static, held once per GPU: 64 KiB of counters,
+ * 512 KiB of (max, sum) pairs, 16 MiB of partial outputs. */
+#define ZZ_STATIC_MAX_UNITS 16384          /* batch * n_kv_heads                          */
+#define ZZ_STATIC_MAX_ROW_ELEMS 32768      /* batch * n_q_heads * head_dim                */
+#define ZZ_STATIC_SCRATCH_BYTES (64 * 1024 + 512 * 1024 + 16 * 1024 * 1024)
 
 enum {
   ZZ_OK = 0,
@@ -144,6 +149,21 @@ int zz_attn_prefill_seq(zz_ctx *ctx, int layer, int b, const void *q, const void
  * phase): call after zz_kv_append(..., 1).  q, out: DEVICE [B, Hq, D].
  * ZZ_ESTATE if a sequence of the layer is empty.  Uses the workspace. */
 int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream);
+
+/* zz_attn_decode for callers that cannot allocate device memory or hand a workspace over at
+ * the time of the call (code under HIP-graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the same launches with the same result, but the split-K partials and
+ * counters go to a static array inside the library (ZZ_STATIC_SCRATCH_BYTES per GPU, resolved
+ * on the call's first use on a device and held until the process ends) instead of the
+ * context's workspace.  The call allocates nothing.  q, out: DEVICE [B, Hq, D], as above.
+ * Limits: batch * n_kv_heads <= ZZ_STATIC_MAX_UNITS and batch * n_q_heads * head_dim <=
+ * ZZ_STATIC_MAX_ROW_ELEMS (128k / batch 4 and 32k / batch 8 at 32 heads of 128 fit), else
+ * ZZ_ENOSPC with nothing launched (zz_last_error_detail says which limit).  Every call on a GPU,
+ * from any context, uses that GPU's one array: the counters are cleared by a small kernel
+ * ahead of the attention launch, the rest is overwritten before it is read; calls that
+ * overlap in time on one GPU (different streams or contexts) race and must be ordered by the
+ * caller. */
+int zz_attn_decode_static(zz_ctx *ctx, int layer, const void *q, void *out, void *stream);
 
 /* One decode step of a layer in a single launch per head kind: appends the newest
  * token's rows (k_new, v_new: DEVICE [B, 1, Hkv, D]) and attends from it (q, out:

@@ -30,7 +30,9 @@ class ZzConfig(C.Structure):
 class ZzError(RuntimeError):
     def __init__(self, code, where):
         self.code = int(code)
-        detail = lib.zz_last_error_detail().decode() if int(code) == ERR["EHIP"] else ""
+        detail = ""
+        if int(code) == ERR["EHIP"] or (int(code) == ERR["ENOSPC"] and where == "zz_attn_decode_static"):
+            detail = lib.zz_last_error_detail().decode()
         super().__init__(f"{where}: {strerror(code)} ({code}) {detail}")
 
 
@@ -53,6 +55,7 @@ def _load():
         "zz_kv_append": (I, [V, I, V, V, I, V]),
         "zz_attn_prefill": (I, [V, I, V, V, V, I, V, V]),
         "zz_attn_decode": (I, [V, I, V, V, V]),
+        "zz_attn_decode_static": (I, [V, I, V, V, V]),
         "zz_decode_step": (I, [V, I, V, V, V, V, V]),
         "zz_kv_append_seq": (I, [V, I, I, V, V, I, V]),
         "zz_attn_prefill_seq": (I, [V, I, I, V, V, V, I, V, V]),
@@ -186,6 +189,9 @@ class Context:
 
     def attn_decode(self, layer, q, out, stream=None):
         self._chk(lib.zz_attn_decode(self._h, layer, _ptr(q), _ptr(out), stream), "zz_attn_decode")
+
+    def attn_decode_static(self, layer, q, out, stream=None):
+        self._chk(lib.zz_attn_decode_static(self._h, layer, _ptr(q), _ptr(out), stream), "zz_attn_decode_static")
 
     def decode_step(self, layer, q, k_new, v_new, out, stream=None):
         self._chk(lib.zz_decode_step(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream),

@@ -544,7 +544,7 @@ int zz_kv_append_seq(zz_ctx *ctx, int layer, int b, const void *k_new, const voi
 // Shared by zz_attn_decode (k_new == nullptr: the newest token is already cached) and
 // zz_decode_step (the newest token is appended by the attention launch itself).
 static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
-                       void *stream) {
+                       void *stream, bool static_scratch = false) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
   const bool fused = k_new != nullptr || v_new != nullptr;
@@ -567,7 +567,29 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
   if (!uniform && c.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
   const int cu = num_cu(ctx);
   int *counters = (int *)(ctx->ws + ctx->lo.ws_counters);
-  if (!ctx->counters_zeroed) {
+  float *part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml), *part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
+  if (static_scratch) {
+    // the library's own array instead of the workspace: [counters | (max, sum) pairs | partial outputs]
+    const int64_t units = (int64_t)c.batch * c.n_kv_heads, elems = (int64_t)c.batch * c.n_q_heads * c.head_dim;
+    if (units > ZZ_STATIC_MAX_UNITS || elems > ZZ_STATIC_MAX_ROW_ELEMS) {
+      std::snprintf(g_detail, sizeof(g_detail),
+                    "zz_attn_decode_static: batch*n_kv_heads = %lld (limit %d), batch*n_q_heads*head_dim = %lld (limit %d)",
+                    (long long)units, ZZ_STATIC_MAX_UNITS, (long long)elems, ZZ_STATIC_MAX_ROW_ELEMS);
+      return ZZ_ENOSPC;
+    }
+    char *base = nullptr;
+    if (hipError_t e = zz_static_scratch(&base)) return hip_failed("address of the static scratch array", e);
+    constexpr size_t counters_bytes = (size_t)ZZ_STATIC_MAX_UNITS * sizeof(int);
+    constexpr size_t ml_bytes = (size_t)(ZZ_STATIC_MAX_ROW_ELEMS / 64) * ZZ_MAX_SPLITS * 2 * sizeof(float);  // head_dim >= 64
+    constexpr size_t o_bytes = (size_t)ZZ_STATIC_MAX_ROW_ELEMS * ZZ_MAX_SPLITS * sizeof(float);
+    static_assert(counters_bytes + ml_bytes + o_bytes == ZZ_STATIC_SCRATCH_BYTES, "regions fill the static array exactly");
+    counters = (int *)base;
+    part_ml = (float *)(base + counters_bytes);
+    part_o = (float *)(base + counters_bytes + ml_bytes);
+    // shared by every context and call on this GPU: cleared every time
+    if (hipError_t e = zz_launch_zero(counters, c.batch * c.n_kv_heads, (hipStream_t)stream))
+      return hip_failed("counter clear kernel", e);
+  } else if (!ctx->counters_zeroed) {
     const bool capturing = zz_stream_is_capturing((hipStream_t)stream);
     if (hipError_t e = zz_launch_zero(counters, c.batch * c.n_kv_heads, (hipStream_t)stream))
       return hip_failed("counter clear kernel", e);
@@ -582,8 +604,8 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
       std::memcpy(p.heads, G.heads, sizeof(p.heads));
       p.q = q;
       p.out = out;
-      p.part_o = (float *)(ctx->ws + ctx->lo.ws_part_o);
-      p.part_ml = (float *)(ctx->ws + ctx->lo.ws_part_ml);
+      p.part_o = part_o;
+      p.part_ml = part_ml;
       p.counters = counters;
       p.k_new = k_new;
       p.v_new = v_new;
@@ -628,6 +650,10 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
 
 int zz_attn_decode(zz_ctx *ctx, int layer, const void *q, void *out, void *stream) {
   return decode_impl(ctx, layer, q, nullptr, nullptr, out, stream);
+}
+
+int zz_attn_decode_static(zz_ctx *ctx, int layer, const void *q, void *out, void *stream) {
+  return decode_impl(ctx, layer, q, nullptr, nullptr, out, stream, true);
 }
 
 int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
@@ -740,7 +766,7 @@ const char *zz_strerror(int code) {
     case ZZ_OK: return "ok";
     case ZZ_EINVAL: return "invalid argument (null pointer, non-positive size or unknown enum)";
     case ZZ_ERANGE: return "layer, head, position or token count out of range";
-    case ZZ_ENOSPC: return "no space: append past max_ctx, or arena/workspace too small";
+    case ZZ_ENOSPC: return "no space: append past max_ctx, arena/workspace too small, or shape beyond the static scratch";
     case ZZ_EALIGN: return "pointer not aligned (tensors 16 bytes, arena and workspace 256 bytes)";
     case ZZ_ESTATE: return "wrong state: empty layer, or the mask for the chosen layout is missing";
     case ZZ_EUNSUPPORTED: return "unsupported shape (head_dim must be 64 or 128, Hq/Hkv <= 16, Hkv <= 64)";

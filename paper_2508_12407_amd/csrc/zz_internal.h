@@ -100,6 +100,9 @@ hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
 hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s);
 hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, int n_wg, void *sink, hipStream_t s);
 int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable
+// Device address, on the current device, of the library's own static scratch array
+// (ZZ_STATIC_SCRATCH_BYTES bytes): resolved once per device, then kept.
+hipError_t zz_static_scratch(char **out);
 bool zz_stream_is_capturing(hipStream_t s);  // true while launches on `s` are recorded into a graph instead of run
 
 #endif

@@ -18,6 +18,8 @@
 // probabilities never move between lanes.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "zz_internal.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -1036,6 +1038,31 @@ int zz_query_num_cu() {
     return 0;
   }
   return n;
+}
+
+// Split-K scratch of zz_attn_decode_static, for callers that may not allocate: one array per
+// GPU, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and clears get the address that call returns, looked up once
+// per device with that device current.
+static __device__ __align__(256) unsigned char scratch[ZZ_STATIC_SCRATCH_BYTES];
+
+hipError_t zz_static_scratch(char **out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static char *ptr[MAX_DEVICES] = {nullptr};
+  *out = nullptr;
+  int dev = 0;
+  if (hipError_t e = hipGetDevice(&dev)) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void *p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr[dev] = (char *)p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
 }
 
 bool zz_stream_is_capturing(hipStream_t s) {

@@ -25,6 +25,10 @@ static int g_launches = 0, g_fail = 0;
 // ---- recorders standing in for the launchers of zz_kernels.hip ----
 const char *hipGetErrorString(hipError_t) { return "stub"; }
 int zz_query_num_cu() { return 256; }
+hipError_t zz_static_scratch(char **out) {
+  *out = (char *)0x40000000;
+  return hipSuccess;
+}
 static bool g_capturing = false;
 bool zz_stream_is_capturing(hipStream_t) { return g_capturing; }
 

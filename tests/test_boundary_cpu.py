@@ -176,6 +176,11 @@ def test_entry_point_error_paths_launch_nothing():
     assert L.zz_attn_decode(h, 5, A, A, None) == E["ERANGE"]
     assert L.zz_attn_decode(h, 0, None, A, None) == E["EINVAL"]
     assert L.zz_attn_decode(h, 0, A, A + 8, None) == E["EALIGN"]
+    assert L.zz_attn_decode_static(h, 0, A, A, None) == E["ESTATE"]
+    assert L.zz_attn_decode_static(h, 5, A, A, None) == E["ERANGE"]
+    assert L.zz_attn_decode_static(h, 0, A, None, None) == E["EINVAL"]
+    assert L.zz_attn_decode_static(h, 0, A + 2, A, None) == E["EALIGN"]
+    assert L.zz_attn_decode_static(None, 0, A, A, None) == E["EINVAL"]
     assert L.zz_decode_step(h, 0, A, None, A, A, None) == E["EINVAL"]
     assert L.zz_decode_step(h, 0, A, A, None, A, None) == E["EINVAL"]
     assert L.zz_decode_step(h, 0, None, A, A, A, None) == E["EINVAL"]
@@ -203,6 +208,22 @@ def test_entry_point_error_paths_launch_nothing():
     assert L.zz_probe_read(h, A + 4, 1 << 20, 1, None) == E["EALIGN"]
     assert L.zz_probe_read(h, A, 1000, 0, None) == E["ERANGE"]
     assert L.zz_reset(None) == E["EINVAL"] and L.zz_destroy(None) == E["EINVAL"]
+
+
+def test_static_scratch_decode_refuses_shapes_beyond_its_array_before_touching_the_gpu():
+    A = 0x30000000
+    for kw in (dict(B=9, Hq=32, Hkv=8, D=128),            # 9 * 32 * 128 elements of output rows > 32768
+               dict(B=1025, Hq=16, Hkv=16, D=64)):        # 16400 (batch, kv head) units > 16384 counters
+        cfg, keep = mk(L=1, lmask=(0,), max_ctx=64, **kw)
+        ctx = fake_ctx(cfg, keep)
+        ctx.set_layer_len(0, 10)
+        assert zb.lib.zz_attn_decode_static(ctx._h, 0, A, A, None) == E["ENOSPC"]
+        assert b"limit" in zb.lib.zz_last_error_detail()
+    hdr = open(os.path.join(ROOT, "include", "zz.h")).read()
+    units, elems, total = (int(eval(re.search(r"#define %s\s+(\(?[0-9 *+]+\)?)" % n, hdr).group(1)))
+                           for n in ("ZZ_STATIC_MAX_UNITS", "ZZ_STATIC_MAX_ROW_ELEMS", "ZZ_STATIC_SCRATCH_BYTES"))
+    # counters + (max, sum) pairs at head_dim 64 + partial outputs, 128 splits each
+    assert total == units * 4 + (elems // 64) * 128 * 2 * 4 + elems * 128 * 4
 
 
 def test_decode_plan_fills_the_chip_and_respects_limits():
