@@ -20,10 +20,12 @@ def attended_pairs(T, streaming, S, W):
     return n * (n + 1) // 2 + (T - n) * n
 
 
-def bench_prefill(args, wname):
+def bench_prefill(args, wname, steps=None, warmup=None):
     import torch
     import zz_inputs
     from paper_2508_12407_amd import binding as zb, harness
+    steps = steps or args.steps
+    warmup = args.warmup if warmup is None else warmup
     w = zz_inputs.WORKLOADS[wname]
     B, Hq, Hkv, D, L, T, C = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_layers, w.context, w.chunk
     lmask = zz_inputs.draw_layer_mask(args.seed, L, w.n_streaming_layers)
@@ -40,7 +42,7 @@ def bench_prefill(args, wname):
 
     kind_counts = {False: [0, 0], True: [0, 0]}
 
-    def one_prompt(record=False, time_kernel=None):
+    def one_prompt(record=False):
         st.ctx.reset()
         vis = cau = 0
         for c in range(n_chunks):
@@ -51,14 +53,7 @@ def bench_prefill(args, wname):
                     cau += b_
                     kind_counts[bool(lmask[l])][0] += a
                     kind_counts[bool(lmask[l])][1] += b_
-                if time_kernel is not None and time_kernel[0] == (c, l):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    st.ctx.attn_prefill(l, q[c], k[c], v[c], C, out, sp)
-                    e1.record()
-                    time_kernel[1].append((e0, e1))
-                else:
-                    st.ctx.attn_prefill(l, q[c], k[c], v[c], C, out, sp)
+                st.ctx.attn_prefill(l, q[c], k[c], v[c], C, out, sp)
                 if record and (c, l) in keep_out:
                     keep_out[(c, l)] = out.float().cpu().numpy()
                 st.ctx.kv_append(l, k[c], v[c], C, sp)
@@ -72,21 +67,32 @@ def bench_prefill(args, wname):
         keep_out[(last, strm[0])] = None
     vis, cau = one_prompt(record=True)
     torch.cuda.synchronize()
-    for _ in range(max(0, args.warmup - 1)):
+    for _ in range(max(0, warmup - 1)):      # the recording pass above was the first warm-up prompt
         one_prompt()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         one_prompt()
     torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / args.steps
+    t_step = (time.perf_counter() - t0) / steps
 
     # dominant kernel: the last chunk of a retrieval layer (n_past = T - C), HIP events on the launch stream
-    tk = ((last, retr[0]), [])
-    for _ in range(3):
-        one_prompt(time_kernel=tk)
+    # (every retrieval layer's last-chunk call is the same launch: all of them are timed, in one more prompt)
+    st.ctx.reset()
+    evs = []
+    for c in range(n_chunks):
+        for l in range(L):
+            if c == last and not lmask[l]:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                st.ctx.attn_prefill(l, q[c], k[c], v[c], C, out, sp)
+                e1.record()
+                evs.append((e0, e1))
+            else:
+                st.ctx.attn_prefill(l, q[c], k[c], v[c], C, out, sp)
+            st.ctx.kv_append(l, k[c], v[c], C, sp)
     torch.cuda.synchronize()
-    t_kernel = float(np.mean([a.elapsed_time(b) for a, b in tk[1]])) * 1e-3
+    t_kernel = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
     pairs_last = sum(i + 1 for i in range(T - C, T))            # retrieval, last chunk, per head
     flop_last = pairs_last * 4 * D * Hq * B
 
@@ -104,21 +110,26 @@ def bench_prefill(args, wname):
         G = Hq // Hkv
         scale = O.default_scale(D)
         max_abs, num, den = 0.0, 0.0, 0.0
-        t_cpu, n_rows = 0.0, 0
+        # one (query row, head) per unit, spread over the host threads the way the decode baseline is
+        threads, host_cores = min(os.cpu_count() or 1, 16), os.cpu_count() or 1
+        units, meta = [], []
         for (c, l), got in keep_out.items():
             streaming = bool(lmask[l])
             for r in rows:
                 i = c * C + r
                 J = O.attended_positions(i, streaming, w.sink, w.window)
                 for h in heads:
-                    t1 = time.perf_counter()
-                    want = O.attention_row(qh[0, r, h], kh[0, J, h // G], vh[0, J, h // G], scale)
-                    t_cpu += time.perf_counter() - t1
-                    n_rows += 1
-                    d = got[0, r, h].astype(np.float64) - want
-                    max_abs = max(max_abs, float(np.abs(d).max()))
-                    num += float((d ** 2).sum())
-                    den += float((want ** 2).sum())
+                    units.append((qh[0, r, h][None, :], kh[0, J, h // G], vh[0, J, h // G]))
+                    meta.append((got, r, h))
+        t1 = time.perf_counter()
+        wants = O.decode_units(units, scale, threads=threads)
+        t_cpu = time.perf_counter() - t1
+        n_rows = len(units)
+        for (got, r, h), want in zip(meta, wants):
+            d = got[0, r, h].astype(np.float64) - want[0]
+            max_abs = max(max_abs, float(np.abs(d).max()))
+            num += float((d ** 2).sum())
+            den += float((want ** 2).sum())
         parity = dict(max_abs=max_abs, rel_l2=float(np.sqrt(num / den)), rows=n_rows)
         # CPU baseline: the oracle's time per sampled row, extrapolated by attended pairs
         pairs_sample = sum(len(O.attended_positions(c * C + r, bool(lmask[l]), w.sink, w.window))
@@ -126,12 +137,14 @@ def bench_prefill(args, wname):
         total_pairs = flop / (4 * D)
         t_cpu_prompt = total_pairs / pairs_sample * t_cpu     # seconds the oracle would need for the whole prompt
         cpu = dict(value=flop / t_cpu_prompt / 1e12, unit="TFLOP/s", ms_per_prompt_token=t_cpu_prompt * 1e3 / (T * B),
-                   cores=1, kind="oracle", measured_on_sample_s=t_cpu, extrapolated=True,
+                   cores=threads, host_cores_visible=host_cores, kind="oracle", measured_on_sample_s=t_cpu,
+                   extrapolated=True,
                    sample=f"{n_rows} (query row, head) pairs of the last chunk of one retrieval and one streaming "
-                          f"layer, {t_cpu:.2f} s single-threaded, extrapolated by attended (query,key) pairs")
+                          f"layer, {t_cpu:.2f} s wall on {threads} threads (the host shows {host_cores} cores; a "
+                          f"one-GPU box's share is 16), extrapolated by attended (query,key) pairs")
     return {
         "metric": "chunked prefill attention TFLOP/s (all layers)", "value": flop / t_step / 1e12, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_step * 1e3,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": t_step * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wname, "layout": "zigzag", "n_layers": L, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "batch": B, "prompt": T, "chunk": C, "sink": w.sink, "window": w.window,

@@ -21,15 +21,15 @@ def make_run(base_cls, w, layout, seed, args, lens):
     class UnequalRun(base_cls):
         """DecodeRun whose sequences sit at different lengths (caches drawn in place)."""
 
-        def step(self, mode="fused"):
-            ctx, sp = self.st.ctx, self.st.stream_ptr()
+        def reset_lengths(self, steps_to_go):
             for l in range(self.w.n_layers):
-                if mode == "fused":
-                    for b, n in enumerate(lens):
-                        ctx.set_seq_len(l, b, n - 1)
-                    ctx.decode_step(l, self.q[l], self.k1[l], self.v1[l], self.out[l], sp)
-                else:
-                    ctx.attn_decode(l, self.q[l], self.out[l], sp)
+                for b, n in enumerate(lens):
+                    self.st.ctx.set_seq_len(l, b, n - steps_to_go)
+
+        def full_lengths(self):
+            for l in range(self.w.n_layers):
+                for b, n in enumerate(lens):
+                    self.st.ctx.set_seq_len(l, b, n)
 
         def bytes_per_step(self):
             w = self.w
@@ -41,11 +41,7 @@ def make_run(base_cls, w, layout, seed, args, lens):
                         total += 2 * (min(n, w.sink + w.window) if streaming else n) * w.head_dim * 2
             return total
 
-    run = UnequalRun(w, layout, seed, args, fill="random")
-    for l in range(w.n_layers):
-        for b, n in enumerate(lens):
-            run.st.ctx.set_seq_len(l, b, n)
-    return run
+    return UnequalRun(w, layout, seed, args, fill="random")
 
 
 def bench_unequal(args, DecodeRun, HBM_PEAK_GBPS):
@@ -58,7 +54,7 @@ def bench_unequal(args, DecodeRun, HBM_PEAK_GBPS):
         run = make_run(DecodeRun, w, "zigzag", args.seed, args, lens)
         t = run.timed(args.steps, args.warmup)
         ev = run.per_step_events(args.steps)
-        t_launch = run.time_retrieval_launch(max(3, args.steps // 4))
+        t_launch = run.time_launches(False, max(3, args.steps // 4))
         nbytes = run.bytes_per_step()
         retr = int(np.flatnonzero(run.lmask == 0)[0])
         ns, tps = run.st.ctx.decode_plan(retr, 0)
