@@ -722,12 +722,16 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
 
   f32x4 acc[NB][NL];
   f32x4 lsum[NB];       // row sums of P, produced by an MFMA against an all-ones operand
-  float mc[NB];         // reference maxima, in log2 units (score * scale * log2 e)
+  float mc[NB];         // reference maxima, in log2 units (score * scale * log2 e); -inf: nothing seen yet
+  float nref[NB];       // what the fast path adds to score * c: minus the reference (0 while it is -inf)
+  float thr[NB];        // exponent above which the reference must be raised: -inf until a key has been seen
   float alpha_pend[NB]; // factor the accumulators still have to be multiplied by
   bool pend = false;
 #pragma unroll
   for (int cb = 0; cb < NB; ++cb) {
     mc[cb] = ZZ_NEG_INF;
+    nref[cb] = 0.f;
+    thr[cb] = ZZ_NEG_INF;
     alpha_pend[cb] = 1.f;
     lsum[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -738,20 +742,35 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
   // ---- the three stages ----
-  auto qk = [&](int n, f32x4(&s0)[NB], f32x4(&s1)[NB]) {
+  // LDS -> registers: the K operands of tile n (token block 0 then 1, per k-step) ...
+  auto read_k = [&](int n, uint4(&kop)[2 * KS]) {
     const uint4 *kt = &s_k[n & (RING - 1)][0] + lane;
+#pragma unroll
+    for (int i = 0; i < 2 * KS; ++i) kop[i] = kt[i * 64];
+  };
+  // ... and V operands [k0, k1) of tile n (one per 16 head dimensions)
+  auto read_v = [&](int n, uint4(&vop)[NL], int k0, int k1) {
+    const uint4 *vt = &s_v[n & (RING - 1)][0] + lane;
+#pragma unroll
+    for (int k = 0; k < NL; ++k)
+      if (k >= k0 && k < k1) vop[k] = vt[k * 64];
+  };
+  auto qk_mfma = [&](const uint4(&kop)[2 * KS], f32x4(&s0)[NB], f32x4(&s1)[NB]) {
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) s0[cb] = s1[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const bf16x8 k0 = as_bf16x8(kt[s * 64]);
-      const bf16x8 k1 = as_bf16x8(kt[(KS + s) * 64]);
 #pragma unroll
       for (int cb = 0; cb < NB; ++cb) {
-        s0[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qop[cb][s], s0[cb], 0, 0, 0);
-        s1[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qop[cb][s], s1[cb], 0, 0, 0);
+        s0[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop[s]), qop[cb][s], s0[cb], 0, 0, 0);
+        s1[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop[KS + s]), qop[cb][s], s1[cb], 0, 0, 0);
       }
     }
+  };
+  auto qk = [&](int n, f32x4(&s0)[NB], f32x4(&s1)[NB]) {
+    uint4 kop[2 * KS];
+    read_k(n, kop);
+    qk_mfma(kop, s0, s1);
   };
   // masks of tile n: -inf into the scores of keys a query may not see, and which of the
   // lane's 8 V tokens exist at all (empty slots may hold NaN bit patterns)
@@ -801,27 +820,60 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       }
     }
   };
-  auto softmax = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB]) {
+  // Softmax step of one tile.  Fast path: x = score * c - reference (one fma per score, computed
+  // anyway), the lane's largest x, one compare per column block: a reference is only raised when
+  // some score of the column exceeds it by 2^8, and no lane can see that without its own x
+  // exceeding the threshold, so while no lane of the wave does, nothing else happens and
+  // P = 2^x.  (The maxima are taken over fma results, which the compiler knows to be
+  // canonical: v_max3 without the quieting v_max x, x in front of every input that it puts
+  // before maxima of raw MFMA results.)  Otherwise, a few times per query: raise().
+  auto exponents = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], float(&x)[NB][8]) {
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        x[cb][r] = fmaf(s0[cb][r], c, nref[cb]);
+        x[cb][4 + r] = fmaf(s1[cb][r], c, nref[cb]);
+      }
+  };
+  // lm[cb]: the lane's largest exponent against the current reference.  New reference of a
+  // column whose largest score exceeds the old one by more than the threshold (always, for the
+  // first key a column sees): that largest score, over all four key groups.
+  auto raise = [&](const float(&lm)[NB]) {
     bool grew = false;
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) {
-      float mx = fmaxf(fmaxf(fmaxf(s0[cb][0], s0[cb][1]), fmaxf(s0[cb][2], s0[cb][3])),
-                       fmaxf(fmaxf(s1[cb][0], s1[cb][1]), fmaxf(s1[cb][2], s1[cb][3])));
-      const float mxc = max_over_kg(mx) * c;
+      const float mxc = max_over_kg(lm[cb]) - nref[cb];     // back to score * c (nref is 0 or -reference)
       const float old = mc[cb];
-      const bool grow = mxc > old + ZZ_RESCALE_THRESHOLD;  // also true for the first visible key (old = -inf)
+      const bool grow = mxc > old + ZZ_RESCALE_THRESHOLD;   // also true for the first visible key (old = -inf)
       const float ref = grow ? mxc : old;
-      const float safe = (ref == ZZ_NEG_INF) ? 0.f : ref;  // a column that has seen nothing yet
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        P[cb][r] = (__bf16)fast_exp2(fmaf(s0[cb][r], c, -safe));
-        P[cb][4 + r] = (__bf16)fast_exp2(fmaf(s1[cb][r], c, -safe));
-      }
-      alpha_pend[cb] = grow ? fast_exp2(old - safe) : 1.f;
+      const bool seen = ref != ZZ_NEG_INF;
+      alpha_pend[cb] = grow ? alpha_pend[cb] * fast_exp2(old - ref) : alpha_pend[cb];   // old = -inf: 0 times an empty sum
       mc[cb] = ref;
+      nref[cb] = seen ? -ref : 0.f;
+      thr[cb] = seen ? ZZ_RESCALE_THRESHOLD : ZZ_NEG_INF;
       grew |= grow;
     }
-    pend = grew;
+    pend |= grew;
+  };
+  auto softmax = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB]) {
+    float x[NB][8], lm[NB];
+    exponents(s0, s1, x);
+    bool trig = false;
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+      lm[cb] = fmaxf(fmaxf(fmaxf(x[cb][0], x[cb][1]), fmaxf(x[cb][2], x[cb][3])),
+                     fmaxf(fmaxf(x[cb][4], x[cb][5]), fmaxf(x[cb][6], x[cb][7])));
+      trig |= lm[cb] > thr[cb];
+    }
+    if (__any(trig)) {
+      raise(lm);
+      exponents(s0, s1, x);
+    }
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) P[cb][e] = (__bf16)fast_exp2(x[cb][e]);
   };
   auto rescale = [&]() {
     if (__any(pend)) {
@@ -830,14 +882,15 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
         lsum[cb] *= alpha_pend[cb];
 #pragma unroll
         for (int k = 0; k < NL; ++k) acc[cb][k] *= alpha_pend[cb];
+        alpha_pend[cb] = 1.f;
       }
+      pend = false;
     }
   };
-  auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned *keep) {
-    const uint4 *vt = &s_v[n & (RING - 1)][0] + lane;
+  auto pv_mfma = [&](const uint4(&vop)[NL], const bf16x8(&P)[NB], const unsigned *keep) {
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
-      uint4 vraw = vt[k * 64];
+      uint4 vraw = vop[k];
       if (keep) {
         vraw.x &= keep[0];
         vraw.y &= keep[1];
@@ -852,6 +905,11 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb)
       lsum[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P[cb], lsum[cb], 0, 0, 0);
+  };
+  auto pv = [&](int n, const bf16x8(&P)[NB], const unsigned *keep) {
+    uint4 vop[NL];
+    read_v(n, vop, 0, NL);
+    pv_mfma(vop, P, keep);
   };
 
   // The values a stage hands to the next iteration are pinned where they are produced:
@@ -898,6 +956,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     issue_fast_v(1);
     qk(1, sB0, sB1);
     softmax(sA0, sA1, PA);
+    rescale();   // the first reference: the factor it brings belongs to the (still empty) sums before tile 0
     pin(sB0, sB1, PA);
     for (int n = 1; n < n_fast; n += 2) {
       // One barrier per two tiles.  At this point K(n+1), K(n+2), V(n-1), V(n) have landed
@@ -905,27 +964,42 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       // whose four ring slots the requests below refill.
       wait_vmcnt<0>();
       __syncthreads();
-      issue_fast_k(n + 3);
-      issue_fast_v(n + 1);
-      issue_fast_k(n + 4);
-      issue_fast_v(n + 2);
+      uint4 kop[2 * KS], vop[NL];
+      // Each half: request the matrix stage's operands from LDS, run the softmax of the current
+      // tile on the vector ALU while they arrive, then the matrix stage with nothing to wait for.
       // odd n: current scores in B, previous P in A
-      rescale();
-      mfma_phase_begin();
-      qk(n + 1, sA0, sA1);
-      pv(n - 1, PA, nullptr);
-      mfma_phase_end();
+      read_k(n + 1, kop);
+      read_v(n - 1, vop, 0, NL / 2);
+      __builtin_amdgcn_sched_barrier(0);
       softmax(sB0, sB1, PB);
-      pin(sA0, sA1, PB);
+      pin(sB0, sB1, PB);
+      mfma_phase_begin();
+      read_v(n - 1, vop, NL / 2, NL);   // these arrive behind the score MFMAs
+      issue_fast_k(n + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      qk_mfma(kop, sA0, sA1);
+      issue_fast_v(n + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      pv_mfma(vop, PA, nullptr);
+      mfma_phase_end();
+      rescale();
       __builtin_amdgcn_sched_barrier(0);
       // even n+1: current scores in A, previous P in B
-      rescale();
-      mfma_phase_begin();
-      qk(n + 2, sB0, sB1);   // for the last pair this is tile n_fast, which the masked loop redoes
-      pv(n, PB, nullptr);
-      mfma_phase_end();
+      read_k(n + 2, kop);   // for the last pair this is tile n_fast, which the masked loop redoes
+      read_v(n, vop, 0, NL / 2);
+      __builtin_amdgcn_sched_barrier(0);
       softmax(sA0, sA1, PA);
-      pin(sB0, sB1, PA);
+      pin(sA0, sA1, PA);
+      mfma_phase_begin();
+      read_v(n, vop, NL / 2, NL);
+      issue_fast_k(n + 4);
+      __builtin_amdgcn_sched_barrier(0);
+      qk_mfma(kop, sB0, sB1);
+      issue_fast_v(n + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      pv_mfma(vop, PB, nullptr);
+      mfma_phase_end();
+      rescale();
       __builtin_amdgcn_sched_barrier(0);
     }
     // drain: the last P is in A
