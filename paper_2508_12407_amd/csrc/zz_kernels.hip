@@ -856,35 +856,6 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     }
     pend |= grew;
   };
-  // The same without control flow, for the pipelined loop (its instructions interleave with the
-  // matrix stage's): P from the current references whatever the exponents are, and whether any
-  // lane saw one above the threshold; if so softmax_redo() raises the references and does the
-  // tile again before anything has used the P computed here.
-  auto softmax_try = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB], float(&lm)[NB]) -> bool {
-    float x[NB][8];
-    exponents(s0, s1, x);
-    bool trig = false;
-#pragma unroll
-    for (int cb = 0; cb < NB; ++cb) {
-      lm[cb] = fmaxf(fmaxf(fmaxf(x[cb][0], x[cb][1]), fmaxf(x[cb][2], x[cb][3])),
-                     fmaxf(fmaxf(x[cb][4], x[cb][5]), fmaxf(x[cb][6], x[cb][7])));
-      trig |= lm[cb] > thr[cb];
-    }
-#pragma unroll
-    for (int cb = 0; cb < NB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) P[cb][e] = (__bf16)fast_exp2(x[cb][e]);
-    return trig;
-  };
-  auto softmax_redo = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB], const float(&lm)[NB]) {
-    float x[NB][8];
-    raise(lm);
-    exponents(s0, s1, x);
-#pragma unroll
-    for (int cb = 0; cb < NB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) P[cb][e] = (__bf16)fast_exp2(x[cb][e]);
-  };
   auto softmax = [&](const f32x4(&s0)[NB], const f32x4(&s1)[NB], bf16x8(&P)[NB]) {
     float x[NB][8], lm[NB];
     exponents(s0, s1, x);
@@ -987,50 +958,6 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     softmax(sA0, sA1, PA);
     rescale();   // the first reference: the factor it brings belongs to the (still empty) sums before tile 0
     pin(sB0, sB1, PA);
-#ifdef ZZ_PF_INTERLEAVE
-    // One instruction stream per half: the softmax of the current tile woven into the matrix stage
-    // (scores of the next tile, P V of the previous one), which it does not depend on.
-    auto half = [&](int n_k, int n_v, const f32x4(&sc0)[NB], const f32x4(&sc1)[NB], bf16x8(&Pc)[NB], f32x4(&sn0)[NB],
-                    f32x4(&sn1)[NB], const bf16x8(&Pp)[NB], int n_dma_k, int n_dma_v) {
-      uint4 kop[2 * KS], vop[NL];
-      float lm[NB];
-      issue_fast_k(n_dma_k);
-      issue_fast_v(n_dma_v);
-      read_k(n_k, kop);
-      read_v(n_v, vop, 0, NL);
-      __builtin_amdgcn_sched_barrier(0);
-      const bool trig = softmax_try(sc0, sc1, Pc, lm);
-#pragma unroll
-      for (int cb = 0; cb < NB; ++cb) asm volatile("" : "+v"(Pc[cb]));   // computed here, not below the branch
-      qk_mfma(kop, sn0, sn1);
-      pv_mfma(vop, Pp, nullptr);
-      // order: the exponents and maxima while the operands arrive, then an exponential behind every score
-      // MFMA, the bf16 conversions behind the first P V MFMAs
-      __builtin_amdgcn_sched_group_barrier(0x002, 10 * NB + 8 * NB, 0);          // VALU: fma, max, compare
-#pragma unroll
-      for (int i = 0; i < 8 * NB; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);                       // transcendental
-      }
-#pragma unroll
-      for (int i = 0; i < 4 * NB; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                       // v_cvt_pk_bf16_f32
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * KS * NB + NL * NB + NB - 12 * NB > 0 ? 2 * KS * NB + NL * NB + NB - 12 * NB : 1, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (__any(trig)) softmax_redo(sc0, sc1, Pc, lm);
-      pin(sn0, sn1, Pc);
-      rescale();
-      __builtin_amdgcn_sched_barrier(0);
-    };
-    for (int n = 1; n < n_fast; n += 2) {
-      wait_vmcnt<0>();
-      __syncthreads();
-      half(n + 1, n - 1, sB0, sB1, PB, sA0, sA1, PA, n + 3, n + 1);   // odd n: current scores in B, previous P in A
-      half(n + 2, n, sA0, sA1, PA, sB0, sB1, PB, n + 4, n + 2);       // even n+1: the other way round
-    }
-#else
     for (int n = 1; n < n_fast; n += 2) {
       // One barrier per two tiles.  At this point K(n+1), K(n+2), V(n-1), V(n) have landed
       // (everything requested one pair ago) and every wave is done with the previous pair,
@@ -1075,7 +1002,6 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       rescale();
       __builtin_amdgcn_sched_barrier(0);
     }
-#endif
     // drain: the last P is in A
     wait_vmcnt<0>();
     __syncthreads();
