@@ -22,9 +22,7 @@ def bench_sweep(args):
     # The paper's own pipeline on synthetic importances: bimodal alpha per (layer, KV head); the
     # heads of smallest alpha are streaming heads (Section 2.1: a different number in every
     # layer), and the transport optimisation (Section 2.2) turns that into whole layers.
-    rng = np.random.default_rng(args.seed)
-    alpha = np.where(rng.random((L, Hkv)) < 0.5, 0.2 * rng.random((L, Hkv)), 0.6 + 0.4 * rng.random((L, Hkv)))
-    alpha = alpha.astype(np.float32)
+    alpha = zz_inputs.draw_head_importances(args.seed, L, Hkv)
     order = np.argsort(alpha, axis=None, kind="stable")
     hmask_q = np.zeros(L * Hkv, np.uint8)
     hmask_q[order[: L * Hkv // 2]] = 1
@@ -48,7 +46,33 @@ def bench_sweep(args):
     oc = torch.empty_like(qc)
     decode_lengths = [1024, 2048, 4096, 8192, 16384, 32768]
     prefill_lengths = [1024, 2048, 4096, 8192, 16384, 32768]
-    res = {"decode_us_per_token": {}, "prefill_us_per_token": {}}
+    res = {"decode_us_per_token": {}, "prefill_us_per_token": {}, "decode_us_per_token_both_orders": {},
+           "prefill_us_per_token_both_orders": {}, "warmup_rounds": {}}
+    TOL = 0.02      # a longer context may not be faster than a shorter one by more than this (run-to-run spread is about 1 %)
+
+    def settle(fn, label):
+        """Runs fn (which returns a time) until two consecutive results agree within 2 %: the first
+        launches after an arena fill and a context creation are not representative."""
+        prev = fn()
+        for rounds in range(1, 12):
+            cur = fn()
+            if abs(cur - prev) <= 0.02 * prev:
+                res["warmup_rounds"][label] = rounds
+                return
+            prev = cur
+        raise RuntimeError("timings of %s do not settle" % label)
+
+    def both_orders(lengths, fn, label):
+        """fn(length) -> time; every length measured in ascending and then in descending order."""
+        up = [fn(x) for x in lengths]
+        down = [fn(x) for x in reversed(lengths)][::-1]
+        mean = [(a + b) / 2 for a, b in zip(up, down)]
+        for i in range(1, len(mean)):
+            if mean[i] < mean[i - 1] * (1 - TOL):
+                raise RuntimeError("%s: latency falls from %.2f to %.2f between %d and %d tokens (ascending %s, descending %s)"
+                                   % (label, mean[i - 1], mean[i], lengths[i - 1], lengths[i], up, down))
+        return mean, {"ascending": up, "descending": down}
+
     for name, kw in layouts.items():
         st = harness.Stack(L, Hq, Hkv, D, B, max_ctx, S, W, max_chunk=C, **kw)
         view = st.arena.view(torch.bfloat16)
@@ -58,25 +82,27 @@ def bench_sweep(args):
             view[a:a + n] = torch.randn(n, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         sp = st.stream_ptr()
         ctx = st.ctx
-        dec = []
-        for d in decode_lengths:
+
+        def decode_time(d, steps=args.steps, warmup=args.warmup):
+            """us per token at context 16k + d: the caches grow by one token per step and reach that
+            context at the last timed step; nothing but zz_decode_step calls inside the timed loop."""
             n_ctx = 16384 + d
+            for l in range(L):
+                ctx.set_layer_len(l, n_ctx - steps - warmup)
 
             def one():
                 for l in range(L):
-                    ctx.set_layer_len(l, n_ctx - 1)
                     ctx.decode_step(l, q1[l], k1[l], v1[l], o1[l], sp)
-            for _ in range(args.warmup):
+            for _ in range(warmup):
                 one()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(steps):
                 one()
             torch.cuda.synchronize()
-            dec.append((time.perf_counter() - t0) / args.steps * 1e6)
-        res["decode_us_per_token"][name] = dec
-        pre = []
-        for T in prefill_lengths:
+            return (time.perf_counter() - t0) / steps * 1e6
+
+        def prefill_time(T, reps=max(1, min(args.steps, 3))):
             def prompt():
                 ctx.reset()
                 for a in range(0, T, C):
@@ -86,15 +112,42 @@ def bench_sweep(args):
                         ctx.kv_append(l, kc, vc, n, sp)
             prompt()
             torch.cuda.synchronize()
-            reps = max(1, min(args.steps, 3))
             t0 = time.perf_counter()
             for _ in range(reps):
                 prompt()
             torch.cuda.synchronize()
-            pre.append((time.perf_counter() - t0) / reps / T * 1e6)
-        res["prefill_us_per_token"][name] = pre
+            return (time.perf_counter() - t0) / reps / T * 1e6
+
+        settle(lambda: decode_time(decode_lengths[0]), name + " decode")
+        res["decode_us_per_token"][name], res["decode_us_per_token_both_orders"][name] = \
+            both_orders(decode_lengths, decode_time, name + " decode")
+        settle(lambda: prefill_time(prefill_lengths[0]), name + " prefill")
+        pre, res["prefill_us_per_token_both_orders"][name] = both_orders(prefill_lengths, lambda T: prefill_time(T) * T, name + " prefill")
+        res["prefill_us_per_token"][name] = [t / T for t, T in zip(pre, prefill_lengths)]   # (monotone in total time, reported per token)
         del st
         torch.cuda.empty_cache()
+
+    # roofline, CPU baseline and parity at the longest decode point of the zigzag layout (same seeded layer mask):
+    # a cache the library built by appending, units sampled as in the default benchmark
+    import bench as B_
+    w_long = zz_inputs.Workload("sweep_longest_point", L, Hq, Hkv, D, B, 16384 + decode_lengths[-1], S, W, L // 2)
+    retr = [l for l in range(L) if not lmask[l]]
+    strm = [l for l in range(L) if lmask[l]]
+    sample = [(l, 0, g) for l in retr[:2] + strm[:2] for g in range(Hkv)]
+    run = B_.DecodeRun(w_long, "zigzag", args.seed, args, fill="append", sample=sample if not args.no_cpu else ())
+    cpu = parity = None
+    if not args.no_cpu:
+        run.step()
+        torch.cuda.synchronize()
+        cpu, parity = B_.cpu_baseline_and_parity(run, args.seed)
+    t_launch = run.time_launches(False, 5)
+    per_launch = B_.layer_bytes(w_long, False, w_long.context)
+    roofline = {"bound": "hbm", "kernel": "zz_decode_kernel<128>, one retrieval layer at the longest sweep point (context %d, batch 1)" % w_long.context,
+                "achieved": per_launch / t_launch / 1e9, "peak": B_.HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": per_launch / t_launch / 1e9 / B_.HBM_PEAK_GBPS, "bytes_per_launch": per_launch,
+                "avg_launch_us": t_launch * 1e6, "traffic": None}
+    del run
+    torch.cuda.empty_cache()
     z, m, r = (np.array(res["decode_us_per_token"][k]) for k in ("zigzag", "mixed", "all_retrieval"))
     return {
         "metric": "per-token decode latency after a 16k prompt, zigzag layout (paper's efficiency experiment shape)",
@@ -104,8 +157,10 @@ def bench_sweep(args):
         "config": {"workload": "paper_efficiency_sweep", "n_layers": L, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "batch": B, "sink": S, "window": W, "streaming_fraction": 0.5, "prompt": 16384,
                    "decode_lengths": decode_lengths, "prefill_lengths": prefill_lengths, "prefill_chunk": C,
-                   "value_is": "zigzag, 1k tokens decoded (context 17408)"},
-        "sweep": res,
+                   "value_is": "zigzag, 1k tokens decoded (context 17408)",
+                   "protocol": "each layout warmed after its arena fill until two consecutive timings agree within 2 %, every "
+                               "length measured in ascending and in descending order (mean reported), monotone growth checked"},
+        "sweep": res, "roofline": roofline, "cpu_baseline": cpu, "parity_sample": parity,
         "zigzag_speedup_over_mixed": (m / z).tolist(), "zigzag_speedup_over_all_retrieval": (r / z).tolist(),
         "transport_zigzag_speedup_over_quantile_mixed":
             (np.array(res["decode_us_per_token"]["mixed_by_quantile"]) /

@@ -460,7 +460,15 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
 #pragma unroll
       for (int j = 0; j < 8; ++j) O = fmaf(v[j], wt[s + j], O);
     }
-    for (; s < ns; ++s) O = fmaf(load_device_coherent(po + (int64_t)s * D), wt[s], O);
+    if (s < ns) {
+      // the last, incomplete group also goes out as eight loads at once (indices past the last split
+      // repeat it with weight zero): single loads would each wait out a whole round trip
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = load_device_coherent(po + (int64_t)min(s + j, ns - 1) * D);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) O = fmaf(v[j], s + j < ns ? wt[s + j] : 0.f, O);
+    }
     ((__bf16 *)p.out)[((int64_t)b * p.n_q_heads + h) * D + d] = (__bf16)O;
   }
   if (threadIdx.x == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -68,6 +68,15 @@ def draw_kvhead_mask(seed: int, n_layers: int, n_kv_heads: int, n_streaming_per_
     return m
 
 
+def draw_head_importances(seed: int, n_layers: int, n_kv_heads: int) -> np.ndarray:
+    """float32[L, Hkv] in [0, 1]: synthetic stand-ins for converged head importances (Section 2.1),
+    bimodal as trained gates are - about half the heads near 0 (below 0.2), the rest above 0.6."""
+    rng = np.random.default_rng(seed)
+    low = rng.random((n_layers, n_kv_heads)) < 0.5
+    a = np.where(low, 0.2 * rng.random((n_layers, n_kv_heads)), 0.6 + 0.4 * rng.random((n_layers, n_kv_heads)))
+    return a.astype(np.float32)
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str
