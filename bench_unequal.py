@@ -44,6 +44,57 @@ def make_run(base_cls, w, layout, seed, args, lens):
     return UnequalRun(w, layout, seed, args, fill="random")
 
 
+def prefill_unequal(args, base, lens, chunk=1024):
+    """A chunk of `chunk` new tokens for every sequence of a batch whose sequences hold different
+    numbers of tokens: one zz_attn_prefill + zz_kv_append per layer for the whole batch (one
+    attention launch per layer) against the same work as one call per sequence."""
+    import torch
+    from paper_2508_12407_amd import harness
+    L, B = 4, len(lens)
+    st = harness.Stack(L, base.n_q_heads, base.n_kv_heads, base.head_dim, B, max(lens) + chunk, base.sink, base.window,
+                       max_chunk=chunk, layer_is_streaming=[0, 1, 0, 1])
+    st.arena.view(torch.bfloat16).normal_()
+    q = torch.randn((B, chunk, base.n_q_heads, base.head_dim), device="cuda").to(torch.bfloat16)
+    k = torch.randn((B, chunk, base.n_kv_heads, base.head_dim), device="cuda").to(torch.bfloat16)
+    v = torch.randn((B, chunk, base.n_kv_heads, base.head_dim), device="cuda").to(torch.bfloat16)
+    out = torch.empty_like(q)
+    sp, ctx = st.stream_ptr(), st.ctx
+
+    def reset():
+        for l in range(L):
+            for b, n in enumerate(lens):
+                ctx.set_seq_len(l, b, n)
+
+    def batched():
+        reset()
+        for l in range(L):
+            ctx.attn_prefill(l, q, k, v, chunk, out, sp)
+            ctx.kv_append(l, k, v, chunk, sp)
+
+    def per_sequence():
+        reset()
+        for l in range(L):
+            for b in range(B):
+                ctx.attn_prefill_seq(l, b, q[b:b + 1], k[b:b + 1], v[b:b + 1], chunk, out[b:b + 1], sp)
+                ctx.kv_append_seq(l, b, k[b:b + 1], v[b:b + 1], chunk, sp)
+
+    res = {}
+    for name, fn in (("one_call_per_layer", batched), ("one_call_per_sequence", per_sequence)):
+        fn()
+        torch.cuda.synchronize()
+        reps = 5
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        res[name + "_ms"] = (time.perf_counter() - t0) / reps * 1e3
+    pairs = sum(sum(i + 1 for i in range(n, n + chunk)) for n in lens)      # retrieval layers: every key up to the query
+    res.update(layers="2 retrieval + 2 streaming", chunk=chunk, lengths=lens,
+               retrieval_flop=2 * pairs * 4 * base.head_dim * base.n_q_heads,
+               speedup=res["one_call_per_sequence_ms"] / res["one_call_per_layer_ms"])
+    return res
+
+
 def bench_unequal(args, DecodeRun, HBM_PEAK_GBPS):
     import torch
     import zz_inputs
@@ -92,4 +143,5 @@ def bench_unequal(args, DecodeRun, HBM_PEAK_GBPS):
                      "frac": first["retrieval_launch"]["frac_of_hbm_peak"], "traffic": None},
         "cpu_baseline": None,
         "length_mixes": points,
+        "prefill_chunk_on_unequal_lengths": {name: prefill_unequal(args, base, lens) for name, lens in LENGTH_MIXES.items()},
     }

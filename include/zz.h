@@ -33,10 +33,11 @@
  *   - Every sequence of the batch has its own length per layer.  The batched calls
  *     advance all B sequences by the same number of tokens, each from its own length;
  *     the *_seq calls advance one sequence, which is how prompts of different lengths
- *     enter a batch.  While all lengths of a layer are equal a batched call is one launch
- *     per head kind; zz_kv_append and zz_attn_prefill on unequal lengths issue one per
- *     sequence, zz_attn_decode and zz_decode_step stay at one launch per head kind
- *     (batches of at most ZZ_MAX_RAGGED_BATCH sequences, else ZZ_EUNSUPPORTED).
+ *     enter a batch.  A batched call is one launch per head kind whether the lengths of the
+ *     layer are equal or not (unequal: the per-sequence lengths travel in the launch's
+ *     arguments), for batches of at most ZZ_MAX_RAGGED_BATCH sequences; larger batches of
+ *     unequal lengths are served one sequence at a time by zz_kv_append and zz_attn_prefill
+ *     and refused (ZZ_EUNSUPPORTED) by zz_attn_decode and zz_decode_step.
  *   - A context must not be used from two host threads at once.
  *   - HIP-graph capture.  Every call may be made on a stream that is being captured: the
  *     launches are recorded instead of run.  The host-side bookkeeping (sequence lengths)

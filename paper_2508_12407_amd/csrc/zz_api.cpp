@@ -425,10 +425,19 @@ int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *
 
 namespace {
 
+// The lengths of sequences [b0, b0 + nb) of a layer as a launch takes them: one common value,
+// or the per-sequence table (at most ZZ_MAX_RAGGED_BATCH sequences).
+void fill_lens(const Layer &L, int b0, int nb, bool ragged, zz_seq_lens *out) {
+  out->ragged = ragged ? 1u : 0u;
+  if (ragged)
+    for (int b = 0; b < nb; ++b) out->len[b] = (uint32_t)L.len[b0 + b];
+}
+
 // Appends n_new tokens to sequences [b0, b0 + nb) of the layer, which share the length
-// `len`; k_new, v_new point at the rows of sequence b0.
+// `len` (ragged: each at its own length, one launch all the same); k_new, v_new point at the
+// rows of sequence b0.
 int append_run(zz_ctx *ctx, Layer &L, int b0, int nb, int64_t len, const void *k_new, const void *v_new, int n_new,
-               void *stream) {
+               void *stream, bool ragged = false) {
   const zz_config &c = ctx->cfg;
   zz_append_params p;
   std::memset(&p, 0, sizeof(p));
@@ -446,14 +455,16 @@ int append_run(zz_ctx *ctx, Layer &L, int b0, int nb, int64_t len, const void *k
   p.sink = c.sink;
   p.window = c.window;
   p.only_group = -1;
-  if (hipError_t e = zz_launch_append(p, (hipStream_t)stream)) return hip_failed("append kernel", e);
+  zz_seq_lens lens;
+  fill_lens(L, b0, nb, ragged, &lens);
+  if (hipError_t e = zz_launch_append(p, lens, (hipStream_t)stream)) return hip_failed("append kernel", e);
   return ZZ_OK;
 }
 
 // Attention of n_new new positions for sequences [b0, b0 + nb), which share the length
-// n_past; all four tensors point at the rows of sequence b0.
+// n_past (ragged: each at its own length); all four tensors point at the rows of sequence b0.
 int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, const void *q, const void *k_new,
-                const void *v_new, int n_new, void *out, void *stream) {
+                const void *v_new, int n_new, void *out, void *stream, bool ragged = false) {
   const zz_config &c = ctx->cfg;
   zz_stage_params sp;
   std::memset(&sp, 0, sizeof(sp));
@@ -466,6 +477,8 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
   sp.n_kv_heads = c.n_kv_heads;
   sp.head_dim = c.head_dim;
   if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
+  zz_seq_lens lens;
+  fill_lens(L, b0, nb, ragged, &lens);
   for (int k = 0; k < 2; ++k) {
     const Group &G = L.grp[k];
     if (G.n_heads == 0) continue;
@@ -487,7 +500,7 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
     p.sink = c.sink;
     p.window = c.window;
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    if (hipError_t e = zz_launch_prefill(p, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+    if (hipError_t e = zz_launch_prefill(p, lens, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
   }
   return ZZ_OK;
 }
@@ -516,6 +529,9 @@ int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, i
   if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;  // the length counter itself is bounded by max_ctx
   if (L.uniform()) {
     rc = append_run(ctx, L, 0, c.batch, L.len[0], k_new, v_new, n_new, stream);
+    if (rc != ZZ_OK) return rc;
+  } else if (c.batch <= ZZ_MAX_RAGGED_BATCH) {
+    rc = append_run(ctx, L, 0, c.batch, 0, k_new, v_new, n_new, stream, true);   // one launch, lengths in its arguments
     if (rc != ZZ_OK) return rc;
   } else {
     for (int b = 0; b < c.batch; ++b) {
@@ -682,6 +698,7 @@ int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, co
   const Layer &L = ctx->lo.layers[layer];
   if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;
   if (L.uniform()) return prefill_run(ctx, L, 0, c.batch, L.len[0], q, k_new, v_new, n_new, out, stream);
+  if (c.batch <= ZZ_MAX_RAGGED_BATCH) return prefill_run(ctx, L, 0, c.batch, 0, q, k_new, v_new, n_new, out, stream, true);
   for (int b = 0; b < c.batch; ++b) {
     rc = prefill_run(ctx, L, b, 1, L.len[b], rows_of(q, b, n_new, c.n_q_heads, c.head_dim),
                      rows_of(k_new, b, n_new, c.n_kv_heads, c.head_dim),

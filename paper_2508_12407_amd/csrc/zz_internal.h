@@ -31,6 +31,14 @@ struct zz_group_dev {
   int32_t pad_;
 };
 
+// Per-sequence lengths of a launch over sequences that differ in length (append, prefill): with
+// ragged != 0 sequence b of the launch has len[b] tokens cached, and the single length in the
+// launch's own parameters (zz_append_params::len, zz_prefill_params::n_past) is not used.
+struct zz_seq_lens {
+  uint32_t ragged;
+  uint32_t len[ZZ_MAX_RAGGED_BATCH];
+};
+
 struct zz_append_params {
   const void *k_new, *v_new;      // [B, n_new, Hkv, D] bf16
   zz_group_dev grp[2];
@@ -92,12 +100,12 @@ struct zz_stage_params {
   int32_t stage_tiles, n_new, batch, n_kv_heads, head_dim;
 };
 
-hipError_t zz_launch_append(const zz_append_params &p, hipStream_t s);
+hipError_t zz_launch_append(const zz_append_params &p, const zz_seq_lens &lens, hipStream_t s);
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
 hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s);
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s);
 hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
-hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s);
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, hipStream_t s);
 hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, int n_wg, void *sink, hipStream_t s);
 int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable
 // Device address, on the current device, of the library's own static scratch array

@@ -61,7 +61,7 @@ __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xo
 // One thread per (batch, new token, kv head, 8-element chunk of the head vector).
 // --------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
+__global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p, zz_seq_lens sl) {
   constexpr int CH = D / 8;
   const int64_t total = (int64_t)p.batch * p.n_new * p.n_kv_heads * CH;
   int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -75,12 +75,13 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
 
   if (p.only_group >= 0 && p.head_group[g] != p.only_group) return;
   const zz_group_dev &G = p.grp[p.head_group[g]];
-  const int64_t pos = p.len + idx;
+  const int64_t len = sl.ragged ? (int64_t)sl.len[b] : p.len;   // tokens the sequence holds already
+  const int64_t pos = len + idx;
   int64_t slot = pos;
   if (G.streaming && pos >= p.sink) {
     // a ring token that a later token of this same call overwrites is never written,
     // so the result does not depend on the order threads run in
-    if (pos + p.window <= p.len + p.n_new - 1) return;
+    if (pos + p.window <= len + p.n_new - 1) return;
     slot = p.sink + (pos - p.sink) % p.window;
   }
   const int64_t src = ((((int64_t)b * p.n_new + idx) * p.n_kv_heads + g) * D) / 8 + c;
@@ -111,9 +112,10 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p) {
 // too (the per-token kernel scatters V in 2-byte pieces, which more than doubles the bytes
 // HBM has to write).  A tile only partly covered by the call keeps the 2-byte stores, so
 // slots that already hold older tokens are not touched.
-// grid (tiles touched, heads of group 0, B).
+// grid (most tiles any sequence touches, heads of group 0, B): with sequences of different
+// lengths each starts at its own tile, and a workgroup past its sequence's last tile has nothing to do.
 template <int D>
-__global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p, int first_tile) {
+__global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p, zz_seq_lens sl) {
   constexpr int CH = D / 8;
   __shared__ unsigned short sv[32][D + 2];
   const zz_group_dev &G = p.grp[0];
@@ -121,14 +123,16 @@ __global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p,
   int g = 0;
   for (int j = 0; j < p.n_kv_heads; ++j)
     if (p.head_group[j] == 0 && p.head_index[j] == hi) g = j;
-  const int64_t tile = (int64_t)first_tile + blockIdx.x;
-  const int64_t s_lo = max(tile * 32, p.len), s_hi = min(tile * 32 + 32, p.len + (int64_t)p.n_new);  // slots == positions
+  const int64_t len = sl.ragged ? (int64_t)sl.len[b] : p.len;
+  const int64_t tile = len / ZZ_TILE_SLOTS + blockIdx.x;
+  if (tile * 32 >= len + p.n_new) return;   // (the whole workgroup)
+  const int64_t s_lo = max(tile * 32, len), s_hi = min(tile * 32 + 32, len + (int64_t)p.n_new);  // slots == positions
   char *tb = G.base + (((int64_t)b * G.n_heads + hi) * G.n_tiles + tile) * (int64_t)(128 * D);
   for (int idx = threadIdx.x; idx < 32 * CH; idx += 256) {
     const int t = idx / CH, c = idx % CH;
     const int64_t slot = tile * 32 + t;
     if (slot < s_lo || slot >= s_hi) continue;
-    const int64_t src = ((((int64_t)b * p.n_new + (slot - p.len)) * p.n_kv_heads + g) * D) / 8 + c;
+    const int64_t src = ((((int64_t)b * p.n_new + (slot - len)) * p.n_kv_heads + g) * D) / 8 + c;
     ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = ((const uint4 *)p.k_new)[src];
     const uint4 vv = ((const uint4 *)p.v_new)[src];
     const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
@@ -604,7 +608,7 @@ __device__ __forceinline__ float max_over_kg(float v) {
 #define ZZ_RESCALE_THRESHOLD 8.0f  // in log2 units
 
 template <int D, int NB>
-__global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, int Gc) {
+__global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, zz_seq_lens sl, int Gc) {
   constexpr int KS = D / 32, NL = D / 16, HALF_U4 = 4 * D, TILE_U4 = 8 * D;
   constexpr int CPW = NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a K part (or V part) each wave brings in
   constexpr int RING = 4;  // power of two: the slot of tile n is n & 3
@@ -617,6 +621,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   const int n_hchunks = G / Gc;
   const int hg = blockIdx.y / n_hchunks, hc = blockIdx.y % n_hchunks;
   const int b = blockIdx.z;
+  const int n_past = sl.ragged ? (int)sl.len[b] : p.n_past;   // tokens this sequence holds already
   const int g = p.heads[hg];
   const int QW = 16 * (NB / Gc);
   // later query blocks see more staged keys: they are dispatched first, so the launch does not end
@@ -624,9 +629,9 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   const int iq_wg = (gridDim.x - 1 - blockIdx.x) * ZZ_WAVES_PER_WG * QW;  // first query index of the workgroup
   const int iq0 = iq_wg + wave * QW;                    // ... of the wave (may lie past n_new: an idle wave
                                                         // computes on masked columns and stores nothing)
-  const int i_lo = p.n_past + iq0;                      // the wave's first query position
-  const int I_lo = p.n_past + iq_wg;                    // the workgroup's range of query positions
-  const int I_hi = p.n_past + min(iq_wg + ZZ_WAVES_PER_WG * QW, p.n_new) - 1;
+  const int i_lo = n_past + iq0;                      // the wave's first query position
+  const int I_lo = n_past + iq_wg;                    // the workgroup's range of query positions
+  const int I_hi = n_past + min(iq_wg + ZZ_WAVES_PER_WG * QW, p.n_new) - 1;
   const bool streaming = p.grp.streaming != 0;
   const int S = p.sink, W = p.window;
   const float c = p.scale_log2e;
@@ -638,13 +643,13 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   // taken first, by the pipelined loop without any mask arithmetic; softmax does not care
   // about the order of keys.  The rest (ragged last cached tile, diagonal and tail tiles,
   // everything of a streaming head) goes through the masked loop.
-  const int occ = streaming ? min(p.n_past, S + W) : p.n_past;
+  const int occ = streaming ? min(n_past, S + W) : n_past;
   const int n_ct = (occ + 31) >> 5;
-  const int k_hi = (I_hi - p.n_past) >> 5;
+  const int k_hi = (I_hi - n_past) >> 5;
   int ks_end = 0, kw_begin = 0;
   if (streaming) {
-    if (p.n_past < S) ks_end = min(k_hi, (S - 1 - p.n_past) >> 5) + 1;  // sink tokens arriving with this chunk
-    const int first_win = I_lo - W + 1 - p.n_past;                      // oldest window token, as a chunk index
+    if (n_past < S) ks_end = min(k_hi, (S - 1 - n_past) >> 5) + 1;  // sink tokens arriving with this chunk
+    const int first_win = I_lo - W + 1 - n_past;                      // oldest window token, as a chunk index
     kw_begin = max(ks_end, first_win > 0 ? first_win >> 5 : 0);
   }
   const int n_tiles = n_ct + ks_end + max(0, k_hi - kw_begin + 1);
@@ -715,7 +720,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     const int h = g * G + hc * Gc + cb % Gc;
     const int iq = iq0 + (cb / Gc) * 16 + col;
     const bool ok = iq < p.n_new;
-    qpos[cb] = ok ? p.n_past + iq : -1;  // -1: sees nothing, output not stored
+    qpos[cb] = ok ? n_past + iq : -1;  // -1: sees nothing, output not stored
     const uint4 *qp = (const uint4 *)p.q + (((int64_t)b * p.n_new + (ok ? iq : 0)) * p.n_q_heads + h) * (D / 8) + kg;
 #pragma unroll
     for (int s = 0; s < KS; ++s) qop[cb][s] = as_bf16x8(qp[4 * s]);
@@ -789,13 +794,13 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     if (ct >= 0)
       plain = !streaming && ct * 32 + 32 <= occ;
     else
-      plain = !streaming && sk * 32 + 32 <= p.n_new && p.n_past + sk * 32 + 31 <= i_lo && iq0 + QW <= p.n_new;
+      plain = !streaming && sk * 32 + 32 <= p.n_new && n_past + sk * 32 + 31 <= i_lo && iq0 + QW <= p.n_new;
     if (plain) {
       keep[0] = keep[1] = keep[2] = keep[3] = 0xffffffffu;
       return;
     }
     int pos[8];
-    const int newest = p.n_past - 1 - S;
+    const int newest = n_past - 1 - S;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int t = (e < 4 ? 0 : 16) + 4 * kg + (e & 3);
@@ -805,7 +810,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
         if (slot < occ) ps = (!streaming || slot < S) ? slot : slot + W * ((newest - (slot - S)) / W);
       } else {
         const int idx = sk * 32 + t;
-        if (idx < p.n_new) ps = p.n_past + idx;
+        if (idx < p.n_new) ps = n_past + idx;
       }
       pos[e] = ps;
     }
@@ -1056,7 +1061,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     if (qpos[cb] < 0) continue;
     const float inv = 1.0f / lsum[cb][0];  // all 16 rows of the ones-product equal the column's sum
     const int h = g * G + hc * Gc + cb % Gc;
-    const int iq = qpos[cb] - p.n_past;
+    const int iq = qpos[cb] - n_past;
     __bf16 *op = (__bf16 *)p.out + (((int64_t)b * p.n_new + iq) * p.n_q_heads + h) * D + 4 * kg;
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
@@ -1156,23 +1161,28 @@ bool zz_stream_is_capturing(hipStream_t s) {
   return st != hipStreamCaptureStatusNone;
 }
 
-hipError_t zz_launch_append(const zz_append_params &p0, hipStream_t s) {
+hipError_t zz_launch_append(const zz_append_params &p0, const zz_seq_lens &lens, hipStream_t s) {
   zz_append_params p = p0;
   // many tokens into never-evicting heads: the tile-wise kernel; streaming heads (at most S+W
   // surviving tokens) and short appends: the per-token kernel
   if (p.n_new >= ZZ_TILE_SLOTS && p.grp[0].n_heads > 0 && p.only_group < 0) {
-    const int first_tile = (int)(p.len / ZZ_TILE_SLOTS);
-    const int last_tile = (int)((p.len + p.n_new - 1) / ZZ_TILE_SLOTS);
-    const dim3 grid(last_tile - first_tile + 1, p.grp[0].n_heads, p.batch);
-    hipError_t e = p.head_dim == 128 ? launch(zz_append_bulk_kernel<128>, grid, dim3(256), s, p, first_tile)
-                                     : launch(zz_append_bulk_kernel<64>, grid, dim3(256), s, p, first_tile);
+    // tiles touched by the sequence that straddles the most of them
+    int64_t most = 0;
+    for (int b = 0; b < (lens.ragged ? p.batch : 1); ++b) {
+      const int64_t len = lens.ragged ? (int64_t)lens.len[b] : p.len;
+      const int64_t tiles = (len + p.n_new - 1) / ZZ_TILE_SLOTS - len / ZZ_TILE_SLOTS + 1;
+      most = tiles > most ? tiles : most;
+    }
+    const dim3 grid((unsigned)most, p.grp[0].n_heads, p.batch);
+    hipError_t e = p.head_dim == 128 ? launch(zz_append_bulk_kernel<128>, grid, dim3(256), s, p, lens)
+                                     : launch(zz_append_bulk_kernel<64>, grid, dim3(256), s, p, lens);
     if (e != hipSuccess || p.grp[1].n_heads == 0) return e;
     p.only_group = 1;
   }
   const int64_t total = (int64_t)p.batch * p.n_new * p.n_kv_heads * (p.head_dim / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  if (p.head_dim == 128) return launch(zz_append_kernel<128>, dim3(blocks), dim3(256), s, p);
-  return launch(zz_append_kernel<64>, dim3(blocks), dim3(256), s, p);
+  if (p.head_dim == 128) return launch(zz_append_kernel<128>, dim3(blocks), dim3(256), s, p, lens);
+  return launch(zz_append_kernel<64>, dim3(blocks), dim3(256), s, p, lens);
 }
 
 hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
@@ -1196,7 +1206,9 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
   p.sink = 0;
   p.window = 1;
   p.only_group = -1;
-  return zz_launch_append(p, s);
+  zz_seq_lens lens;
+  lens.ragged = 0;   // every sequence's staging area is empty
+  return zz_launch_append(p, lens, s);
 }
 
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s) {
@@ -1232,12 +1244,12 @@ hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, 
   return launch(zz_probe_read_kernel<false>, dim3(n_wg), dim3(256), s, (const uint4 *)buf, n_blocks, (uint4 *)sink);
 }
 
-hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t s) {
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, hipStream_t s) {
   constexpr int NB = ZZ_PREFILL_NB;
   const int G = p.group_size;
   const int Gc = zz_prefill_heads_per_wave(G);  // heads per wave, divides NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
   const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
-  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, Gc);
-  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, Gc);
+  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, lens, Gc);
+  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, lens, Gc);
 }

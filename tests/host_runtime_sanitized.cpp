@@ -32,19 +32,28 @@ hipError_t zz_static_scratch(char **out) {
 static bool g_capturing = false;
 bool zz_stream_is_capturing(hipStream_t) { return g_capturing; }
 
-hipError_t zz_launch_append(const zz_append_params &p, hipStream_t) {
+static int g_append_launches = 0, g_prefill_launches = 0;
+hipError_t zz_launch_append(const zz_append_params &p, const zz_seq_lens &lens, hipStream_t) {
   ++g_launches;
+  ++g_append_launches;
+  EXPECT(!lens.ragged || p.batch <= ZZ_MAX_RAGGED_BATCH);
   EXPECT(p.n_new > 0 && p.batch > 0 && p.len >= 0);
   for (int g = 0; g < p.n_kv_heads; ++g) EXPECT(p.head_index[g] < p.grp[p.head_group[g]].n_heads);
   return hipSuccess;
 }
+static int g_stage_launches = 0;
 hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t) {
   ++g_launches;
+  ++g_stage_launches;
   EXPECT(p.n_new > 0 && (p.n_new + 31) / 32 <= p.stage_tiles);
   return hipSuccess;
 }
-hipError_t zz_launch_prefill(const zz_prefill_params &p, hipStream_t) {
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, hipStream_t) {
   ++g_launches;
+  ++g_prefill_launches;
+  EXPECT(!lens.ragged || p.batch <= ZZ_MAX_RAGGED_BATCH);
+  if (lens.ragged)
+    for (int b = 0; b < p.batch; ++b) EXPECT(((int64_t)lens.len[b] + 31) / 32 <= p.grp.n_tiles || p.grp.streaming);
   EXPECT(p.n_new > 0 && p.n_past >= 0 && p.batch > 0 && p.grp.n_heads > 0);
   EXPECT(((int64_t)p.n_past + 31) / 32 <= p.grp.n_tiles || p.grp.streaming);
   return hipSuccess;
@@ -201,10 +210,19 @@ int main(int argc, char **argv) {
           for (int b = 0; b < B; ++b) EXPECT(zz_seq_len(ctx, layer, b) == before[b] + 1);
           int ns = 0, tps = 0;
           for (int grp = 0; grp < 2; ++grp) EXPECT(zz_decode_plan(ctx, layer, grp, &ns, &tps) == ZZ_OK);
-          const int before_launches = g_launches;
+          // unequal lengths or not: one attention launch per head kind behind one staging launch, and
+          // one append launch (two for a layer of both kinds when the tile-wise kernel takes the retrieval heads)
+          const int kinds = zz_layer_launches(ctx, layer);
+          g_stage_launches = g_prefill_launches = 0;
           EXPECT(zz_attn_prefill(ctx, layer, T, T, T, 100, T, nullptr) == ZZ_OK);
+          EXPECT(g_prefill_launches == kinds && g_stage_launches == 1);
+          g_append_launches = 0;
           EXPECT(zz_kv_append(ctx, layer, T, T, 100, nullptr) == ZZ_OK);
-          EXPECT(g_launches > before_launches);
+          EXPECT(g_append_launches == 1);
+          g_append_launches = 0;
+          EXPECT(zz_kv_append(ctx, layer, T, T, 1, nullptr) == ZZ_OK);
+          EXPECT(g_append_launches == 1);
+          for (int b = 0; b < B; ++b) EXPECT(zz_set_seq_len(ctx, layer, b, zz_seq_len(ctx, layer, b) - 1) == ZZ_OK);
           const int b = (int)(rnd() % B);
           EXPECT(zz_attn_prefill_seq(ctx, layer, b, T, T, T, 512, T, nullptr) == ZZ_OK);
           EXPECT(zz_kv_append_seq(ctx, layer, b, T, T, 512, nullptr) == ZZ_OK);
