@@ -266,6 +266,15 @@ int zz_tune(zz_ctx *ctx, int key, int value);
  * is the largest of those counts. */
 int zz_decode_plan(const zz_ctx *ctx, int layer, int group, int *n_splits, int *tiles_per_split);
 
+/* Debug build.  A library compiled with -DZZ_DEBUG_BOUNDS (libzz_debug.so, built next to the
+ * regular one) checks every cache-slot write of the append kernels and of the fused append
+ * against the slot capacity and the byte range of the head's region before it stores; a write
+ * that fails the check is dropped and counted in one 32-bit word of the workspace, at the
+ * byte offset zz_debug_word_offset returns (0 for an invalid config).  The caller zeroes the
+ * word and reads it back; the regular build never touches it.  zz_is_debug_build: 1 or 0. */
+size_t zz_debug_word_offset(const zz_config *cfg);
+int zz_is_debug_build(void);
+
 /* Measurement aid, not part of the method: streams `bytes` (rounded down to 16 KiB) of DEVICE
  * memory `buf` through one workgroup per compute unit with the decode kernel's access pattern
  * and discards them; nontemporal != 0 uses the same non-temporal loads as the decode kernel.

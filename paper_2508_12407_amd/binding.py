@@ -8,7 +8,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libzz.so")
+# (ZZ_LIBRARY=libzz_debug.so selects the bounds-checking debug build of the same sources, for the test that runs it)
+LIB_PATH = os.path.join(_PKG, os.environ.get("ZZ_LIBRARY", "libzz.so"))
 
 ZZ_ZIGZAG, ZZ_MIXED = 0, 1
 ZZ_TILE_SLOTS = 32
@@ -71,6 +72,8 @@ def _load():
         "zz_prefill_tile_counts": (I, [V, I, I, P(I64), P(I64)]),
         "zz_transport_select": (I, [P(C.c_float), I, I, C.c_float, C.c_float, P(C.c_uint8), P(C.c_double)]),
         "zz_probe_read": (I, [V, V, C.c_size_t, I, V]),
+        "zz_debug_word_offset": (C.c_size_t, [P(ZzConfig)]),
+        "zz_is_debug_build": (I, []),
         "zz_strerror": (C.c_char_p, [I]),
         "zz_last_error_detail": (C.c_char_p, []),
     }

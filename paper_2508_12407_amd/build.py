@@ -8,6 +8,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libzz.so")
+DEBUG_LIB_PATH = os.path.join(PKG_DIR, "libzz_debug.so")   # the same sources with -DZZ_DEBUG_BOUNDS (checked slot writes)
 CLIENT_PATH = os.path.join(PKG_DIR, "zz_c_abi_client")   # the torch-free client of the C ABI (tests/c_abi_client.cpp)
 SOURCES = [os.path.join(CSRC, "zz_api.cpp"), os.path.join(CSRC, "zz_transport.cpp"), os.path.join(CSRC, "zz_kernels.hip")]
 
@@ -21,18 +22,20 @@ def hipcc() -> str:
 
 def build(verbose: bool = False) -> str:
     """Compile for gfx950.  Packed-FP32 instruction selection is switched off for
-    device code (the host pass prints a harmless "not a recognized feature" note)."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-I" + os.path.join(ROOT, "include"),
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-inline-asm",
-           *SOURCES, "-o", LIB_PATH]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or res.returncode != 0:
-        print(" ".join(cmd))
-        print(res.stdout)
-        print("\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l))
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libzz.so")
+    device code (the host pass prints a harmless "not a recognized feature" note).
+    Builds the library, its bounds-checking debug variant and the C client."""
+    for out, extra in ((LIB_PATH, []), (DEBUG_LIB_PATH, ["-DZZ_DEBUG_BOUNDS"])):
+        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-I" + os.path.join(ROOT, "include"),
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-inline-asm",
+               *extra, *SOURCES, "-o", out]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if verbose or res.returncode != 0:
+            print(" ".join(cmd))
+            print(res.stdout)
+            print("\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l))
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed building " + os.path.basename(out))
     build_c_client(verbose)
     return LIB_PATH
 

@@ -42,7 +42,7 @@ struct Layer {
 struct Layout {
   std::vector<Layer> layers;
   size_t arena_bytes = 0;
-  size_t ws_part_o = 0, ws_part_ml = 0, ws_counters = 0, ws_stage = 0, ws_bytes = 0;
+  size_t ws_part_o = 0, ws_part_ml = 0, ws_counters = 0, ws_debug = 0, ws_stage = 0, ws_bytes = 0;
   int stage_tiles = 0;
 };
 
@@ -105,6 +105,8 @@ void build_layout(const zz_config *c, Layout *lo) {
   w += align_up((size_t)c->batch * c->n_q_heads * ZZ_MAX_SPLITS * 2 * sizeof(float), 256);
   lo->ws_counters = w;
   w += align_up((size_t)c->batch * c->n_kv_heads * sizeof(int), 256);
+  lo->ws_debug = w;   // one word, written only by a bounds-checking debug build
+  w += 256;
   lo->ws_stage = w;
   lo->stage_tiles = (int)ceil_div(c->max_chunk, ZZ_TILE_SLOTS);
   w += align_up((size_t)c->batch * c->n_kv_heads * lo->stage_tiles * tile, 256);
@@ -148,7 +150,7 @@ zz_group_dev dev_group(const zz_ctx *ctx, const Group &G, int b0 = 0) {
   d.n_heads = G.n_heads;
   d.n_tiles = G.n_tiles;
   d.streaming = G.streaming ? 1 : 0;
-  d.pad_ = 0;
+  d.capacity = (int32_t)G.capacity;
   return d;
 }
 
@@ -382,6 +384,21 @@ int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv
   return (int64_t)G.base + tile_index * (int64_t)kv_tile_bytes(c.head_dim) + elem * 2;
 }
 
+size_t zz_debug_word_offset(const zz_config *cfg) {
+  if (validate(cfg) != ZZ_OK) return 0;
+  Layout lo;
+  build_layout(cfg, &lo);
+  return lo.ws_debug;
+}
+
+int zz_is_debug_build(void) {
+#ifdef ZZ_DEBUG_BOUNDS
+  return 1;
+#else
+  return 0;
+#endif
+}
+
 int zz_tune(zz_ctx *ctx, int key, int value) {
   if (!ctx) return ZZ_EINVAL;
   switch (key) {
@@ -455,6 +472,7 @@ int append_run(zz_ctx *ctx, Layer &L, int b0, int nb, int64_t len, const void *k
   p.sink = c.sink;
   p.window = c.window;
   p.only_group = -1;
+  p.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
   zz_seq_lens lens;
   fill_lens(L, b0, nb, ragged, &lens);
   if (hipError_t e = zz_launch_append(p, lens, (hipStream_t)stream)) return hip_failed("append kernel", e);
@@ -476,6 +494,7 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
   sp.batch = nb;
   sp.n_kv_heads = c.n_kv_heads;
   sp.head_dim = c.head_dim;
+  sp.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
   if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
   zz_seq_lens lens;
   fill_lens(L, b0, nb, ragged, &lens);
@@ -631,6 +650,7 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
       p.head_dim = c.head_dim;
       p.group_size = c.n_q_heads / c.n_kv_heads;
       p.scale_log2e = ctx->scale * 1.4426950408889634f;
+      p.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
     };
     if (uniform) {
       zz_decode_params p;

@@ -28,7 +28,7 @@ struct zz_group_dev {
   int32_t n_heads;     // KV heads in the group
   int32_t n_tiles;     // tiles per (batch, head) = ceil(capacity / 32)
   int32_t streaming;   // 1: sink + ring slots; 0: slot == position
-  int32_t pad_;
+  int32_t capacity;    // slots per (batch, head): max_ctx or S + W (n_tiles is that, rounded up to whole tiles)
 };
 
 // Per-sequence lengths of a launch over sequences that differ in length (append, prefill): with
@@ -48,6 +48,7 @@ struct zz_append_params {
   int32_t n_new, batch, n_kv_heads, head_dim;
   int32_t sink, window;
   int32_t only_group;             // -1: every head; 0/1: only the heads of that group (the rest belongs to another launch)
+  uint32_t *debug_word;           // a build with ZZ_DEBUG_BOUNDS counts here the slot writes it refused; otherwise unused
 };
 
 struct zz_decode_params {
@@ -65,6 +66,7 @@ struct zz_decode_params {
   int32_t tiles_per_split, n_splits;
   int32_t batch, n_q_heads, n_kv_heads, head_dim, group_size;
   float scale_log2e;              // softmax scale * log2(e)
+  uint32_t *debug_word;           // as in zz_append_params (the fused append writes a slot too)
 };
 
 // Decode over sequences of different lengths: the workgroups of all sequences form one
@@ -98,6 +100,7 @@ struct zz_stage_params {
   const void *k_new, *v_new;      // [B, n_new, Hkv, D]
   char *stage;
   int32_t stage_tiles, n_new, batch, n_kv_heads, head_dim;
+  uint32_t *debug_word;
 };
 
 hipError_t zz_launch_append(const zz_append_params &p, const zz_seq_lens &lens, hipStream_t s);

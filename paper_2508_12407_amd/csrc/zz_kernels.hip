@@ -56,6 +56,14 @@ __device__ __forceinline__ uint4 pick(bool c, uint4 a, uint4 b) {
 
 __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
+// Debug build (-DZZ_DEBUG_BOUNDS): every cache-slot write is checked against the head's slot
+// capacity and tile count first; a write that fails is dropped and counted, never issued.
+#ifdef ZZ_DEBUG_BOUNDS
+#define ZZ_SLOT_WRITE_OK(ok, word) ((ok) ? true : ((word) ? (atomicAdd((word), 1u), false) : false))
+#else
+#define ZZ_SLOT_WRITE_OK(ok, word) true
+#endif
+
 // --------------------------------------------------------------------------
 // Append / evict: scatter new K, V rows into their tiles.
 // One thread per (batch, new token, kv head, 8-element chunk of the head vector).
@@ -90,6 +98,7 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p, zz_s
 
   const int64_t tile = slot / ZZ_TILE_SLOTS;
   const int t = (int)(slot % ZZ_TILE_SLOTS);
+  if (!ZZ_SLOT_WRITE_OK(slot >= 0 && slot < G.capacity && tile < G.n_tiles && p.head_index[g] < G.n_heads, p.debug_word)) return;
   char *tb = G.base + (((int64_t)b * G.n_heads + p.head_index[g]) * G.n_tiles + tile) * (int64_t)(128 * D);
   // K: 16-byte chunk c of the row -> [t/16][c][t%16]
   ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = kv;
@@ -127,6 +136,8 @@ __global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p,
   const int64_t tile = len / ZZ_TILE_SLOTS + blockIdx.x;
   if (tile * 32 >= len + p.n_new) return;   // (the whole workgroup)
   const int64_t s_lo = max(tile * 32, len), s_hi = min(tile * 32 + 32, len + (int64_t)p.n_new);  // slots == positions
+  if (!ZZ_SLOT_WRITE_OK(s_lo >= 0 && s_hi <= G.capacity && tile < G.n_tiles && hi < G.n_heads, threadIdx.x == 0 ? p.debug_word : nullptr))
+    return;   // (the whole workgroup: the condition is the same for all its threads)
   char *tb = G.base + (((int64_t)b * G.n_heads + hi) * G.n_tiles + tile) * (int64_t)(128 * D);
   for (int idx = threadIdx.x; idx < 32 * CH; idx += 256) {
     const int t = idx / CH, c = idx % CH;
@@ -259,6 +270,7 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
     for (int i = 0; i < NL; ++i) vnew[i] = vp[16 * i];
   }
   auto patch_new_token = [&](uint4(&kv)[2 * NL]) __attribute__((always_inline)) {
+    if (!ZZ_SLOT_WRITE_OK(new_slot < p.grp.capacity && tile_new < p.grp.n_tiles, lane == 0 ? p.debug_word : nullptr)) return;
     const int tn = new_slot & 31, jn = tn & 15, kgn = jn >> 2;
     const int en = 4 * (tn >> 4) + (tn & 3);  // which of the lane's 8 V tokens
     uint4 *tile = const_cast<uint4 *>(tiles) - lane + (int64_t)tile_new * TILE_U4;
@@ -409,12 +421,20 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
   // collects the four waves, then one thread counts the workgroup in.  The
   // workgroup that completes the count reads every partial of the unit back with
   // device-coherent loads, writes the output and re-arms the counter.
+  // What this leans on, all of it gfx950 behaviour rather than the language's memory model: a store
+  // with the device-coherent policy is acknowledged (vmcnt drops) only once it is visible to
+  // every compute unit of the device; the counter is a device-scope atomic executed in order after
+  // that wait; the merging workgroup's loads carry the same policy and so never hit a line an L2 of
+  // another XCD kept.  The signal fences keep the compiler from moving the stores, the wait, the
+  // increment and the loads across one another (the asm statement's memory clobber does the same).
   __shared__ int s_is_last;
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int *counter = p.counters + b * p.n_kv_heads + g;
   if (threadIdx.x == 0)
     s_is_last = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_splits - 1);
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __syncthreads();
   if (!s_is_last) return;
   // Three short phases instead of one thread walking all splits (each device-coherent
@@ -1193,7 +1213,9 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
   p.grp[0].base = sp.stage;
   p.grp[0].n_heads = sp.n_kv_heads;
   p.grp[0].n_tiles = sp.stage_tiles;
+  p.grp[0].capacity = sp.stage_tiles * ZZ_TILE_SLOTS;
   p.grp[0].streaming = 0;
+  p.debug_word = sp.debug_word;
   for (int g = 0; g < sp.n_kv_heads; ++g) {
     p.head_group[g] = 0;
     p.head_index[g] = (uint8_t)g;

@@ -141,6 +141,40 @@ def test_decode_split_merge_is_race_free_with_far_more_workgroups_than_cus():
     check(outs[128][7], want, "split merge vs oracle")
 
 
+def test_decode_split_merge_stress_every_launch_checked_against_itself_unsplit():
+    """Second guard for the ordering of the cross-workgroup merge (partials stored device-coherently,
+    each wave waiting for its stores before the workgroup is counted in): 600 launches over changing
+    split counts, workgroups per compute unit and queries, on a small cache (so that launches are
+    short and the merge is most of each), every output compared on the device with the unsplit result of
+    the same query, stopping at the first mismatch.  The merge is deterministic for a given split count,
+    and differs from the unsplit sum only by rounding: any larger difference is a stale or early read."""
+    H, zb = _harness()
+    B, Hq, Hkv, D, S, W, T = 4, 32, 8, 128, 64, 256, 2048
+    q, k, v = zz_inputs.make_qkv(62, B, T, Hq, Hkv, D)
+    st = H.Stack(1, Hq, Hkv, D, B, T, S, W, layer_is_streaming=[0], poison_arena=True)
+    st.append(0, H.to_dev_bf16(k), H.to_dev_bf16(v))
+    qs = H.to_dev_bf16(q[:, :200].transpose(1, 0, 2, 3).copy())
+    st.ctx.tune(zb.TUNE_DECODE_SPLITS, 1)
+    ref = torch.empty_like(qs)
+    for i in range(qs.shape[0]):
+        st.decode(0, qs[i], ref[i])
+    ref = ref.float()
+    scale = ref.abs().max().item()
+    launches = 0
+    for splits, wg_per_cu in ((64, 1), (7, 1), (33, 4), (2, 1), (61, 2), (16, 8)):
+        st.ctx.tune(zb.TUNE_DECODE_SPLITS, splits)
+        st.ctx.tune(zb.TUNE_DECODE_WG_PER_CU, wg_per_cu)
+        o = torch.empty_like(qs[:100])
+        for i in range(100):
+            st.decode(0, qs[(i * 7 + splits) % 200], o[i])
+        torch.cuda.synchronize()
+        for i in range(100):
+            d = (o[i].float() - ref[(i * 7 + splits) % 200]).abs().max().item()
+            assert d <= 2.0 ** -7 * scale, ("first mismatch", splits, wg_per_cu, i, d, scale)
+        launches += 100
+    assert launches == 600
+
+
 @pytest.mark.parametrize("D,Hq,Hkv", [(64, 4, 2), (128, 32, 8), (128, 4, 4)])
 def test_decode_step_equals_append_then_decode(D, Hq, Hkv):
     """zz_decode_step (append fused into the attention launch) against the two-call
