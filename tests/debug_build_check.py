@@ -27,7 +27,7 @@ def main():
     q, k, v = zz_inputs.make_qkv(5, B, T, Hq, Hkv, D)
     kd, vd, qd = H.to_dev_bf16(k), H.to_dev_bf16(v), H.to_dev_bf16(q)
     hm = np.array([[0, 1], [1, 0], [0, 0], [1, 1]], np.uint8)
-    st = H.Stack(4, Hq, Hkv, D, B, T, S, W, max_chunk=128, layout=zb.ZZ_MIXED, kvhead_is_streaming=hm, poison_arena=True)
+    st = H.Stack(4, Hq, Hkv, D, B, T + 8, S, W, max_chunk=128, layout=zb.ZZ_MIXED, kvhead_is_streaming=hm, poison_arena=True)
     _, off = debug_word(st)
     st.workspace[off:off + 4].zero_()
     # chunks that straddle the sink edge, wrap the ring, exceed the window; single tokens; fused steps;
@@ -45,7 +45,7 @@ def main():
     for l in range(4):
         for g in range(Hkv):
             streaming = bool(hm[l, g])
-            cap = O.cache_capacity(streaming, S, W, T)
+            cap = O.cache_capacity(streaming, S, W, T + 8)
             for which, X in ((0, k), (1, v)):
                 img, valid = O.expected_cache(zz_inputs.bf16_bits(X), 360, streaming, S, W, cap)
                 slots = np.flatnonzero(valid)
