@@ -48,6 +48,17 @@ TRANSPORT = ("oracle/zz_transport_oracle.py", ["tests/test_transport.py", "-k", 
     ("becomes_streaming = i in chosen", "becomes_streaming = i not in chosen"),
 ])
 
+ROPE = ("oracle/zz_rope_oracle.py", ["tests/test_rope_oracle_pins.py"], [
+    ("out[..., :half] = lo * c - hi * s", "out[..., :half] = lo * c + hi * s"),
+    ("out[..., half:] = hi * c + lo * s", "out[..., half:] = hi * c - lo * s"),
+    ("out[..., :half] = lo * c - hi * s", "out[..., :half] = lo * s - hi * c"),
+    ("out[..., half:] = hi * c + lo * s", "out[..., half:] = lo * c + hi * s"),
+    ("lo, hi = x[..., :half], x[..., half:]", "lo, hi = x[..., 0::2], x[..., 1::2]"),
+    ("out[..., :half] = lo * c - hi * s", "out[..., :half] = lo * c"),
+    ("c = np.asarray(cos, dtype=np.float64)[pos][:, :, None, :]", "c = np.asarray(cos, dtype=np.float64)[pos[:1]][:, :, None, :]"),
+    ("s = np.asarray(sin, dtype=np.float64)[pos][:, :, None, :]", "s = np.asarray(sin, dtype=np.float64)[pos + 0 * pos[:, :1]][:, ::-1][:, :, None, :]"),
+])
+
 CONFTEST = '''import os, sys
 HERE = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, %r)      # the package (library binding) and nothing the copy shadows
@@ -61,7 +72,7 @@ def run_pins(workdir, target, pins, mutation):
     """Copy what the pins need into workdir, plant the mutation (None: none), run them."""
     for rel in ("oracle", "tests/golden"):
         shutil.copytree(os.path.join(ROOT, rel), os.path.join(workdir, rel))
-    for rel in ("zz_inputs.py", "tests/test_oracle_pins.py", "tests/test_transport.py"):
+    for rel in ("zz_inputs.py", "tests/test_oracle_pins.py", "tests/test_transport.py", "tests/test_rope_oracle_pins.py"):
         shutil.copy(os.path.join(ROOT, rel), os.path.join(workdir, rel))
     open(os.path.join(workdir, "tests", "conftest.py"), "w").write(CONFTEST)
     if mutation is not None:
@@ -76,7 +87,7 @@ def run_pins(workdir, target, pins, mutation):
     return r.returncode, r.stdout[-600:] + r.stderr[-300:]
 
 
-@pytest.mark.parametrize("group", [ATTENTION, TRANSPORT], ids=["attention", "transport"])
+@pytest.mark.parametrize("group", [ATTENTION, TRANSPORT, ROPE], ids=["attention", "transport", "rope"])
 def test_every_planted_mistake_fails_a_pin(group, tmp_path):
     target, pins, mutations = group
     rc, out = run_pins(str(tmp_path / "clean"), target, pins, None)
