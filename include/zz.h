@@ -176,6 +176,18 @@ int zz_attn_decode_static(zz_ctx *ctx, int layer, const void *q, void *out, void
 int zz_decode_step(zz_ctx *ctx, int layer, const void *q, const void *k_new, const void *v_new, void *out,
                    void *stream);
 
+/* Rotary position encoding at append (not in the paper, whose model, Section 3.1, uses it; a step
+ * next to the hot path fused in, in the spirit of Section 1's concern with per-layer overhead).
+ * cos_table, sin_table: DEVICE fp32 [rows][D/2], 16-byte aligned, caller-owned, alive while set.
+ * Once set, every K row that enters the context - zz_kv_append, the chunk of zz_attn_prefill,
+ * the newest token of zz_decode_step - is rotated before it is stored or attended: element i
+ * with element i + D/2 by the angle of row p of the tables, p the token's absolute position in
+ * its sequence (streaming caches keep the positions the tokens had: no re-indexing), computed
+ * in fp32 as x cos - y sin / x cos + y sin and rounded to bf16.  V and q are taken as given: the
+ * caller rotates q.  A call that would need a row >= rows returns ZZ_ERANGE and launches nothing.
+ * (NULL, NULL, 0) switches it off again; the default. */
+int zz_set_rope_tables(zz_ctx *ctx, const float *cos_table, const float *sin_table, int64_t rows);
+
 /* Tokens appended to the layer so far (of its longest sequence, if they differ), or a
  * negative error code.  Host bookkeeping only (build convention): a streaming layer counts
  * every token it has seen, not the S + W it still holds, because the slot of the next token

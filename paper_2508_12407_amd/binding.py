@@ -65,6 +65,7 @@ def _load():
         "zz_layer_len": (I64, [V, I]),
         "zz_set_layer_len": (I, [V, I, I64]),
         "zz_layer_launches": (I, [V, I]),
+        "zz_set_rope_tables": (I, [V, V, V, I64]),
         "zz_slot_of": (I64, [P(ZzConfig), I, I, I64]),
         "zz_kv_elem_offset": (I64, [V, I, I, I, I, I64, I]),
         "zz_tune": (I, [V, I, I]),
@@ -205,6 +206,10 @@ class Context:
 
     def set_layer_len(self, layer, n):
         self._chk(lib.zz_set_layer_len(self._h, layer, n), "zz_set_layer_len")
+
+    def set_rope_tables(self, cos, sin, rows):
+        self._rope = (cos, sin)      # the tables stay alive with the context
+        self._chk(lib.zz_set_rope_tables(self._h, _ptr(cos), _ptr(sin), rows), "zz_set_rope_tables")
 
     def layer_launches(self, layer):
         return int(lib.zz_layer_launches(self._h, layer))

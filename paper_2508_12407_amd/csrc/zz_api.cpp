@@ -139,6 +139,8 @@ struct zz_ctx {
   // is replayed, so it does not count).  The merge re-arms a counter it has used.
   bool counters_zeroed = false;
   std::vector<int64_t> seen, tiles;  // per-sequence scratch of the decode call (sized at create: no heap work per call)
+  const float *rope_cos = nullptr, *rope_sin = nullptr;   // caller's tables [rope_rows][D/2], or null: K is stored as given
+  int64_t rope_rows = 0;
 };
 
 namespace {
@@ -348,6 +350,21 @@ int zz_set_seq_len(zz_ctx *ctx, int layer, int b, int64_t len) {
   return ZZ_OK;
 }
 
+int zz_set_rope_tables(zz_ctx *ctx, const float *cos_table, const float *sin_table, int64_t rows) {
+  if (!ctx) return ZZ_EINVAL;
+  if (!cos_table && !sin_table && rows == 0) {
+    ctx->rope_cos = ctx->rope_sin = nullptr;
+    ctx->rope_rows = 0;
+    return ZZ_OK;
+  }
+  if (!cos_table || !sin_table || rows < 1) return ZZ_EINVAL;
+  if (misaligned(cos_table, 16) || misaligned(sin_table, 16)) return ZZ_EALIGN;
+  ctx->rope_cos = cos_table;
+  ctx->rope_sin = sin_table;
+  ctx->rope_rows = rows;
+  return ZZ_OK;
+}
+
 int zz_layer_launches(const zz_ctx *ctx, int layer) {
   int rc = check_layer(ctx, layer);
   if (rc != ZZ_OK) return rc;
@@ -473,6 +490,8 @@ int append_run(zz_ctx *ctx, Layer &L, int b0, int nb, int64_t len, const void *k
   p.window = c.window;
   p.only_group = -1;
   p.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
+  p.rope_cos = ctx->rope_cos;
+  p.rope_sin = ctx->rope_sin;
   zz_seq_lens lens;
   fill_lens(L, b0, nb, ragged, &lens);
   if (hipError_t e = zz_launch_append(p, lens, (hipStream_t)stream)) return hip_failed("append kernel", e);
@@ -495,9 +514,12 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
   sp.n_kv_heads = c.n_kv_heads;
   sp.head_dim = c.head_dim;
   sp.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
-  if (hipError_t e = zz_launch_stage(sp, (hipStream_t)stream)) return hip_failed("staging kernel", e);
+  sp.rope_cos = ctx->rope_cos;
+  sp.rope_sin = ctx->rope_sin;
+  sp.n_past = n_past;
   zz_seq_lens lens;
   fill_lens(L, b0, nb, ragged, &lens);
+  if (hipError_t e = zz_launch_stage(sp, lens, (hipStream_t)stream)) return hip_failed("staging kernel", e);
   for (int k = 0; k < 2; ++k) {
     const Group &G = L.grp[k];
     if (G.n_heads == 0) continue;
@@ -546,6 +568,7 @@ int zz_kv_append(zz_ctx *ctx, int layer, const void *k_new, const void *v_new, i
   Layer &L = ctx->lo.layers[layer];
   const zz_config &c = ctx->cfg;
   if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;  // the length counter itself is bounded by max_ctx
+  if (ctx->rope_cos && L.longest() + n_new > ctx->rope_rows) return ZZ_ERANGE;
   if (L.uniform()) {
     rc = append_run(ctx, L, 0, c.batch, L.len[0], k_new, v_new, n_new, stream);
     if (rc != ZZ_OK) return rc;
@@ -570,6 +593,7 @@ int zz_kv_append_seq(zz_ctx *ctx, int layer, int b, const void *k_new, const voi
   if (n_new == 0) return ZZ_OK;
   Layer &L = ctx->lo.layers[layer];
   if (L.len[b] + n_new > ctx->cfg.max_ctx) return ZZ_ENOSPC;
+  if (ctx->rope_cos && L.len[b] + n_new > ctx->rope_rows) return ZZ_ERANGE;
   rc = append_run(ctx, L, b, 1, L.len[b], k_new, v_new, n_new, stream);
   if (rc != ZZ_OK) return rc;
   L.len[b] += n_new;
@@ -598,6 +622,7 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
   }
   const bool uniform = longest == shortest;
   if (fused && longest + 1 > c.max_ctx) return ZZ_ENOSPC;
+  if (fused && ctx->rope_cos && longest + 1 > ctx->rope_rows) return ZZ_ERANGE;
   if (shortest + add <= 0) return ZZ_ESTATE;
   if (!uniform && c.batch > ZZ_MAX_RAGGED_BATCH) return ZZ_EUNSUPPORTED;
   const int cu = num_cu(ctx);
@@ -651,12 +676,16 @@ static int decode_impl(zz_ctx *ctx, int layer, const void *q, const void *k_new,
       p.group_size = c.n_q_heads / c.n_kv_heads;
       p.scale_log2e = ctx->scale * 1.4426950408889634f;
       p.debug_word = (uint32_t *)(ctx->ws + ctx->lo.ws_debug);
+      p.rope_cos = fused ? ctx->rope_cos : nullptr;
+      p.rope_sin = fused ? ctx->rope_sin : nullptr;
+      p.new_pos = 0;
     };
     if (uniform) {
       zz_decode_params p;
       fill(p);
       const int64_t len = len0 + add;
       p.new_slot = fused ? (int32_t)slot_rule(G.streaming, len - 1, c.sink, c.window) : -1;
+      p.new_pos = (int32_t)(len - 1);
       p.n_valid = (int)occupied(ctx, G, len);
       p.n_tiles_valid = (int)ceil_div(p.n_valid, ZZ_TILE_SLOTS);
       plan_decode(ctx, cu, G, len, &p.n_splits, &p.tiles_per_split);
@@ -717,6 +746,7 @@ int zz_attn_prefill(zz_ctx *ctx, int layer, const void *q, const void *k_new, co
   const zz_config &c = ctx->cfg;
   const Layer &L = ctx->lo.layers[layer];
   if (L.longest() + n_new > c.max_ctx) return ZZ_ENOSPC;
+  if (ctx->rope_cos && L.longest() + n_new > ctx->rope_rows) return ZZ_ERANGE;
   if (L.uniform()) return prefill_run(ctx, L, 0, c.batch, L.len[0], q, k_new, v_new, n_new, out, stream);
   if (c.batch <= ZZ_MAX_RAGGED_BATCH) return prefill_run(ctx, L, 0, c.batch, 0, q, k_new, v_new, n_new, out, stream, true);
   for (int b = 0; b < c.batch; ++b) {
@@ -737,6 +767,7 @@ int zz_attn_prefill_seq(zz_ctx *ctx, int layer, int b, const void *q, const void
   if (n_new == 0) return ZZ_OK;
   const Layer &L = ctx->lo.layers[layer];
   if (L.len[b] + n_new > ctx->cfg.max_ctx) return ZZ_ENOSPC;
+  if (ctx->rope_cos && L.len[b] + n_new > ctx->rope_rows) return ZZ_ERANGE;
   return prefill_run(ctx, L, b, 1, L.len[b], q, k_new, v_new, n_new, out, stream);
 }
 

@@ -49,6 +49,8 @@ struct zz_append_params {
   int32_t sink, window;
   int32_t only_group;             // -1: every head; 0/1: only the heads of that group (the rest belongs to another launch)
   uint32_t *debug_word;           // a build with ZZ_DEBUG_BOUNDS counts here the slot writes it refused; otherwise unused
+  const float *rope_cos, *rope_sin;  // [rows][D/2] fp32 tables, or null: K rows are rotated by their position's angles
+  int32_t stage;                  // 1: the chunk goes to slots 0.. of an empty area (prefill staging); positions still count from len
 };
 
 struct zz_decode_params {
@@ -67,6 +69,8 @@ struct zz_decode_params {
   int32_t batch, n_q_heads, n_kv_heads, head_dim, group_size;
   float scale_log2e;              // softmax scale * log2(e)
   uint32_t *debug_word;           // as in zz_append_params (the fused append writes a slot too)
+  const float *rope_cos, *rope_sin;  // as in zz_append_params: rotation of the newest token's K row
+  int32_t new_pos;                // position of the newest token (its row of the tables)
 };
 
 // Decode over sequences of different lengths: the workgroups of all sequences form one
@@ -101,13 +105,15 @@ struct zz_stage_params {
   char *stage;
   int32_t stage_tiles, n_new, batch, n_kv_heads, head_dim;
   uint32_t *debug_word;
+  const float *rope_cos, *rope_sin;
+  int64_t n_past;                 // position of the chunk's first token (equal lengths)
 };
 
 hipError_t zz_launch_append(const zz_append_params &p, const zz_seq_lens &lens, hipStream_t s);
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
 hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s);
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s);
-hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t s);
+hipError_t zz_launch_stage(const zz_stage_params &p, const zz_seq_lens &lens, hipStream_t s);
 hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, hipStream_t s);
 hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, int n_wg, void *sink, hipStream_t s);
 int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable

@@ -64,6 +64,35 @@ __device__ __forceinline__ float xor_lanes(float v, int mask) { return __shfl_xo
 #define ZZ_SLOT_WRITE_OK(ok, word) true
 #endif
 
+// Rotary position encoding of eight consecutive elements of a K row: `own` (elements d .. d+7) turned
+// together with `partner` (the elements D/2 away) by the angles of the row's position,
+//     lower half:  x cos - y sin        upper half:  x cos + y sin        (y: the partner element)
+// in fp32 from the bf16 inputs and the caller's fp32 tables, rounded to bf16 (nearest even).
+// cs, sn: the eight table entries of the pair indices d mod D/2 .. +7.
+__device__ __forceinline__ uint4 rope_chunk(uint4 own, uint4 partner, const float *cs, const float *sn, bool upper) {
+  const float4 c0 = *(const float4 *)cs, c1 = *(const float4 *)(cs + 4);
+  const float4 s0 = *(const float4 *)sn, s1 = *(const float4 *)(sn + 4);
+  const float c[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+  const float sg[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+  const unsigned xo[4] = {own.x, own.y, own.z, own.w}, yo[4] = {partner.x, partner.y, partner.z, partner.w};
+  unsigned r[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    unsigned packed = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int j = 2 * w + h;
+      const float x = __builtin_bit_cast(float, h ? (xo[w] & 0xffff0000u) : (xo[w] << 16));
+      const float y = __builtin_bit_cast(float, h ? (yo[w] & 0xffff0000u) : (yo[w] << 16));
+      const float v = fmaf(upper ? y : -y, sg[j], x * c[j]);
+      const __bf16 vb = (__bf16)v;
+      packed |= (unsigned)__builtin_bit_cast(unsigned short, vb) << (16 * h);
+    }
+    r[w] = packed;
+  }
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 // --------------------------------------------------------------------------
 // Append / evict: scatter new K, V rows into their tiles.
 // One thread per (batch, new token, kv head, 8-element chunk of the head vector).
@@ -84,17 +113,23 @@ __global__ __launch_bounds__(256) void zz_append_kernel(zz_append_params p, zz_s
   if (p.only_group >= 0 && p.head_group[g] != p.only_group) return;
   const zz_group_dev &G = p.grp[p.head_group[g]];
   const int64_t len = sl.ragged ? (int64_t)sl.len[b] : p.len;   // tokens the sequence holds already
-  const int64_t pos = len + idx;
+  const int64_t pos = (p.stage ? 0 : len) + idx;                 // where the token goes (staging: an empty area)
   int64_t slot = pos;
   if (G.streaming && pos >= p.sink) {
     // a ring token that a later token of this same call overwrites is never written,
     // so the result does not depend on the order threads run in
-    if (pos + p.window <= len + p.n_new - 1) return;
+    if (pos + p.window <= len + p.n_new - 1) return;   // (never a staging launch: its heads do not evict)
     slot = p.sink + (pos - p.sink) % p.window;
   }
   const int64_t src = ((((int64_t)b * p.n_new + idx) * p.n_kv_heads + g) * D) / 8 + c;
-  const uint4 kv = ((const uint4 *)p.k_new)[src];
+  uint4 kv = ((const uint4 *)p.k_new)[src];
   const uint4 vv = ((const uint4 *)p.v_new)[src];
+  if (p.rope_cos) {
+    const bool upper = c >= CH / 2;
+    const uint4 partner = ((const uint4 *)p.k_new)[upper ? src - CH / 2 : src + CH / 2];
+    const int64_t row = (len + idx) * (D / 2) + 8 * (c % (CH / 2));
+    kv = rope_chunk(kv, partner, p.rope_cos + row, p.rope_sin + row, upper);
+  }
 
   const int64_t tile = slot / ZZ_TILE_SLOTS;
   const int t = (int)(slot % ZZ_TILE_SLOTS);
@@ -132,10 +167,11 @@ __global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p,
   int g = 0;
   for (int j = 0; j < p.n_kv_heads; ++j)
     if (p.head_group[j] == 0 && p.head_index[j] == hi) g = j;
-  const int64_t len = sl.ragged ? (int64_t)sl.len[b] : p.len;
+  const int64_t held = sl.ragged ? (int64_t)sl.len[b] : p.len;   // tokens the sequence holds: position of the chunk's first token
+  const int64_t len = p.stage ? 0 : held;                         // slot of the chunk's first token (staging: an empty area)
   const int64_t tile = len / ZZ_TILE_SLOTS + blockIdx.x;
   if (tile * 32 >= len + p.n_new) return;   // (the whole workgroup)
-  const int64_t s_lo = max(tile * 32, len), s_hi = min(tile * 32 + 32, len + (int64_t)p.n_new);  // slots == positions
+  const int64_t s_lo = max(tile * 32, len), s_hi = min(tile * 32 + 32, len + (int64_t)p.n_new);  // slots == positions (+ held - len)
   if (!ZZ_SLOT_WRITE_OK(s_lo >= 0 && s_hi <= G.capacity && tile < G.n_tiles && hi < G.n_heads, threadIdx.x == 0 ? p.debug_word : nullptr))
     return;   // (the whole workgroup: the condition is the same for all its threads)
   char *tb = G.base + (((int64_t)b * G.n_heads + hi) * G.n_tiles + tile) * (int64_t)(128 * D);
@@ -144,7 +180,14 @@ __global__ __launch_bounds__(256) void zz_append_bulk_kernel(zz_append_params p,
     const int64_t slot = tile * 32 + t;
     if (slot < s_lo || slot >= s_hi) continue;
     const int64_t src = ((((int64_t)b * p.n_new + (slot - len)) * p.n_kv_heads + g) * D) / 8 + c;
-    ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = ((const uint4 *)p.k_new)[src];
+    uint4 kv = ((const uint4 *)p.k_new)[src];
+    if (p.rope_cos) {
+      const bool upper = c >= CH / 2;
+      const uint4 partner = ((const uint4 *)p.k_new)[upper ? src - CH / 2 : src + CH / 2];
+      const int64_t row = (held + (slot - len)) * (D / 2) + 8 * (c % (CH / 2));
+      kv = rope_chunk(kv, partner, p.rope_cos + row, p.rope_sin + row, upper);
+    }
+    ((uint4 *)tb)[((t >> 4) * CH + c) * 16 + (t & 15)] = kv;
     const uint4 vv = ((const uint4 *)p.v_new)[src];
     const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
@@ -209,7 +252,8 @@ __device__ __forceinline__ bf16x8 softmax_step(const float (&x)[8], float &m, fl
 // --------------------------------------------------------------------------
 template <int D, int WAVES>
 __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int split, const int b, const int n_valid,
-                                            const int n_tiles_valid, const int n_splits, const int new_slot) {
+                                            const int n_tiles_valid, const int n_splits, const int new_slot,
+                                            const int new_pos) {
   constexpr int KS = D / 32;      // MFMA k-steps over the head dimension
   constexpr int NL = D / 16;      // 1 KiB loads in the K part (= 2*KS) and in the V part
   constexpr int TILE_U4 = 8 * D;  // uint4 per KV tile
@@ -266,6 +310,18 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
     const unsigned short *vp = (const unsigned short *)p.v_new + ((int64_t)b * p.n_kv_heads + g) * D + col;
 #pragma unroll
     for (int s = 0; s < KS; ++s) knew[s] = kp[4 * s];
+    if (p.rope_cos) {
+      // chunk 4s + kg of the row pairs with the chunk D/16 further on or back: the same lane's s +- KS/2
+      uint4 turned[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bool upper = s >= KS / 2;
+        const int64_t row = (int64_t)new_pos * (D / 2) + 8 * ((4 * s + kg) % (D / 16));
+        turned[s] = rope_chunk(knew[s], knew[upper ? s - KS / 2 : s + KS / 2], p.rope_cos + row, p.rope_sin + row, upper);
+      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s) knew[s] = turned[s];
+    }
 #pragma unroll
     for (int i = 0; i < NL; ++i) vnew[i] = vp[16 * i];
   }
@@ -500,7 +556,7 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
 
 template <int D>
 __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
-  decode_body<D, 4>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
+  decode_body<D, 4>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot, p.new_pos);
 }
 
 // Short caches (one workgroup per unit, at most 16 tiles: a streaming head's sink + window):
@@ -509,7 +565,7 @@ __global__ __launch_bounds__(256) void zz_decode_kernel(zz_decode_params p) {
 // through LDS) instead of two or three round trips in a row.  Group sizes up to 8.
 template <int D>
 __global__ __launch_bounds__(512) void zz_decode_short_kernel(zz_decode_params p) {
-  decode_body<D, 8>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot);
+  decode_body<D, 8>(p, blockIdx.x, blockIdx.z, p.n_valid, p.n_tiles_valid, p.n_splits, p.new_slot, p.new_pos);
 }
 
 // Sequences of different lengths: grid (all workgroups of all sequences, heads of the group).
@@ -528,7 +584,7 @@ __device__ __forceinline__ void decode_ragged_body(const zz_decode_ragged_params
   const int n_valid = streaming ? min(len, p.sink + p.window) : len;
   const int newest = len - 1;
   const int slot = (!streaming || newest < p.sink) ? newest : p.sink + (newest - p.sink) % p.window;
-  decode_body<D, WAVES>(p.u, split, b, n_valid, (n_valid + 31) >> 5, n_splits, p.u.new_slot >= 0 ? slot : -1);
+  decode_body<D, WAVES>(p.u, split, b, n_valid, (n_valid + 31) >> 5, n_splits, p.u.new_slot >= 0 ? slot : -1, newest);
 }
 
 template <int D>
@@ -1188,8 +1244,8 @@ hipError_t zz_launch_append(const zz_append_params &p0, const zz_seq_lens &lens,
   if (p.n_new >= ZZ_TILE_SLOTS && p.grp[0].n_heads > 0 && p.only_group < 0) {
     // tiles touched by the sequence that straddles the most of them
     int64_t most = 0;
-    for (int b = 0; b < (lens.ragged ? p.batch : 1); ++b) {
-      const int64_t len = lens.ragged ? (int64_t)lens.len[b] : p.len;
+    for (int b = 0; b < (lens.ragged && !p.stage ? p.batch : 1); ++b) {
+      const int64_t len = p.stage ? 0 : lens.ragged ? (int64_t)lens.len[b] : p.len;
       const int64_t tiles = (len + p.n_new - 1) / ZZ_TILE_SLOTS - len / ZZ_TILE_SLOTS + 1;
       most = tiles > most ? tiles : most;
     }
@@ -1205,8 +1261,9 @@ hipError_t zz_launch_append(const zz_append_params &p0, const zz_seq_lens &lens,
   return launch(zz_append_kernel<64>, dim3(blocks), dim3(256), s, p, lens);
 }
 
-hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
-  // staging is an append of the chunk into an empty, never-evicting cache of its own
+hipError_t zz_launch_stage(const zz_stage_params &sp, const zz_seq_lens &lens, hipStream_t s) {
+  // staging is an append of the chunk into an empty, never-evicting cache of its own; the sequences'
+  // lengths only matter as positions (rotation angles)
   zz_append_params p = {};
   p.k_new = sp.k_new;
   p.v_new = sp.v_new;
@@ -1220,7 +1277,10 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
     p.head_group[g] = 0;
     p.head_index[g] = (uint8_t)g;
   }
-  p.len = 0;
+  p.len = sp.n_past;
+  p.stage = 1;
+  p.rope_cos = sp.rope_cos;
+  p.rope_sin = sp.rope_sin;
   p.n_new = sp.n_new;
   p.batch = sp.batch;
   p.n_kv_heads = sp.n_kv_heads;
@@ -1228,8 +1288,6 @@ hipError_t zz_launch_stage(const zz_stage_params &sp, hipStream_t s) {
   p.sink = 0;
   p.window = 1;
   p.only_group = -1;
-  zz_seq_lens lens;
-  lens.ragged = 0;   // every sequence's staging area is empty
   return zz_launch_append(p, lens, s);
 }
 

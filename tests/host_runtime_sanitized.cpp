@@ -42,7 +42,7 @@ hipError_t zz_launch_append(const zz_append_params &p, const zz_seq_lens &lens, 
   return hipSuccess;
 }
 static int g_stage_launches = 0;
-hipError_t zz_launch_stage(const zz_stage_params &p, hipStream_t) {
+hipError_t zz_launch_stage(const zz_stage_params &p, const zz_seq_lens &, hipStream_t) {
   ++g_launches;
   ++g_stage_launches;
   EXPECT(p.n_new > 0 && (p.n_new + 31) / 32 <= p.stage_tiles);

@@ -207,6 +207,14 @@ def test_entry_point_error_paths_launch_nothing():
     assert L.zz_probe_read(None, A, 1 << 20, 1, None) == E["EINVAL"]
     assert L.zz_probe_read(h, A + 4, 1 << 20, 1, None) == E["EALIGN"]
     assert L.zz_probe_read(h, A, 1000, 0, None) == E["ERANGE"]
+    # rotary tables: both or neither, aligned, at least one row; positions past the last row are refused
+    assert L.zz_set_rope_tables(h, A, None, 8) == E["EINVAL"] and L.zz_set_rope_tables(h, A, A, 0) == E["EINVAL"]
+    assert L.zz_set_rope_tables(h, A + 4, A, 8) == E["EALIGN"] and L.zz_set_rope_tables(None, A, A, 8) == E["EINVAL"]
+    assert L.zz_set_rope_tables(h, A, A, 8) == 0
+    assert L.zz_kv_append(h, 0, A, A, 9, None) == E["ERANGE"] and ctx.layer_len(0) == 0
+    assert L.zz_attn_prefill(h, 0, A, A, A, 9, A, None) == E["ERANGE"]
+    assert L.zz_set_layer_len(h, 0, 8) == 0 and L.zz_decode_step(h, 0, A, A, A, A, None) == E["ERANGE"]
+    assert L.zz_set_rope_tables(h, None, None, 0) == 0 and L.zz_reset(h) == 0
     assert L.zz_reset(None) == E["EINVAL"] and L.zz_destroy(None) == E["EINVAL"]
 
 
