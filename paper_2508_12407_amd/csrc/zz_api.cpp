@@ -109,7 +109,9 @@ void build_layout(const zz_config *c, Layout *lo) {
   w += 256;
   lo->ws_stage = w;
   lo->stage_tiles = (int)ceil_div(c->max_chunk, ZZ_TILE_SLOTS);
-  w += align_up((size_t)c->batch * c->n_kv_heads * lo->stage_tiles * tile, 256);
+  // (two more tiles behind the last head's area: the prefill kernel requests tiles a fixed distance ahead
+  // and its last requests, which nobody reads, may run that far past a head's staged chunk)
+  w += align_up(((size_t)c->batch * c->n_kv_heads * lo->stage_tiles + 2) * tile, 256);
   lo->ws_bytes = w;
 }
 

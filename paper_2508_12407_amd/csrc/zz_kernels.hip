@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "zz_internal.h"
 
@@ -772,22 +773,6 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     const uint4 *src = tile_src(n, ct, sk) + HALF_U4;
     dma_to_lds<CPW>(src, lane_off, lds_v0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
   };
-  // The same for the pipelined loop, whose tiles are two plain runs (cached, then staged):
-  // branch-free scalar arithmetic.  Past its last tile the loop keeps requesting that tile
-  // again (the loads in flight stay constant; the masked loop requests what it needs itself).
-  auto fast_src = [&](int n) -> const uint4 * {
-    const int m = min(n, n_fast - 1);
-    const uint4 *a = ctiles + (int64_t)m * TILE_U4;
-    const uint4 *b2 = stiles + (int64_t)(m - nc_full) * TILE_U4;
-    return m < nc_full ? a : b2;
-  };
-  auto issue_fast_k = [&](int n) {
-    dma_to_lds<CPW>(fast_src(n), lane_off, lds_k0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
-  };
-  auto issue_fast_v = [&](int n) {
-    dma_to_lds<CPW>(fast_src(n) + HALF_U4, lane_off, lds_v0 + (unsigned)(n & (RING - 1)) * (HALF_U4 * 16));
-  };
-
   // ---- per column block: head, query position, Q operand ----
   int qpos[NB];
   bf16x8 qop[NB][KS];
@@ -1004,6 +989,10 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   // The values a stage hands to the next iteration are pinned where they are produced:
   // being pure register arithmetic, the compiler would otherwise sink the whole softmax
   // step down to the first use of P, one barrier later, and undo the overlap.
+  auto pin_p = [&](bf16x8(&P)[NB]) {
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) asm volatile("" : "+v"(P[cb]));
+  };
   auto pin = [&](f32x4(&s0)[NB], f32x4(&s1)[NB], bf16x8(&P)[NB]) {
 #pragma unroll
     for (int cb = 0; cb < NB; ++cb) asm volatile("" : "+v"(s0[cb]), "+v"(s1[cb]), "+v"(P[cb]));
@@ -1026,71 +1015,93 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   // Iteration n computes scores of tile n+1 and P V of tile n-1, then softmax of tile n; the loop body
   // is two iterations (registers alternate between the A and B sets) behind one barrier.
   // Ring slot of tile t is t & 3, for K parts and V parts alike.
+  // Every instruction of the loop costs its wave an issue slot, scalar ones and waits included, and
+  // the two waves of a SIMD hardly issue side by side: the body is kept short.  Tile requests walk the
+  // sequence with a running pointer each (K requests run ahead of V requests), the body is written
+  // for a constant ring slot (two copies: tiles 1,2 mod 4 and 3,0 mod 4), all operands of a matrix
+  // stage are requested before the softmax next to it and waited for once.
   // kq / vq (masked loop): next tile whose K part / V part has not been requested yet.
   int kq = 0, vq = 0;
   if (n_fast > 0) {
     f32x4 sA0[NB], sA1[NB], sB0[NB], sB1[NB];
     bf16x8 PA[NB], PB[NB];
-    issue_fast_k(0);
-    issue_fast_k(1);
+    // The fast sequence is the full cached tiles, then staged tiles; requests past its end (the loop
+    // requests a fixed distance ahead) go on into staged tiles nobody reads: valid memory (the staging
+    // area is padded for them), landing in ring slots the loop is done with.
+    const char *const cached_end = (const char *)(ctiles + (int64_t)nc_full * TILE_U4);
+    const char *pk = nc_full > 0 ? (const char *)ctiles : (const char *)stiles;
+    const char *pvv = pk;
+    auto next_tile = [&](const char *&ptr) -> const char * {
+      const char *cur = ptr;
+      ptr += TILE_U4 * 16;
+      ptr = ptr == cached_end ? (const char *)stiles : ptr;
+      return cur;
+    };
+    auto request_k = [&](int slot) { dma_to_lds<CPW>(next_tile(pk), lane_off, lds_k0 + (unsigned)slot * (HALF_U4 * 16)); };
+    auto request_v = [&](int slot) {
+      dma_to_lds<CPW>(next_tile(pvv) + HALF_U4 * 16, lane_off, lds_v0 + (unsigned)slot * (HALF_U4 * 16));
+    };
+    request_k(0);
+    request_k(1);
     wait_vmcnt<CPW>();  // K(0)
     __syncthreads();
-    issue_fast_k(2);
-    issue_fast_v(0);
+    request_k(2);
+    request_v(0);
     qk(0, sA0, sA1);
     // n = 0: no P V yet
     wait_vmcnt<2 * CPW>();
     __syncthreads();
-    issue_fast_k(3);
-    issue_fast_v(1);
+    request_k(3);
+    request_v(1);
     qk(1, sB0, sB1);
     softmax(sA0, sA1, PA);
     rescale();   // the first reference: the factor it brings belongs to the (still empty) sums before tile 0
     pin(sB0, sB1, PA);
-    for (int n = 1; n < n_fast; n += 2) {
-      // One barrier per two tiles.  At this point K(n+1), K(n+2), V(n-1), V(n) have landed
-      // (everything requested one pair ago) and every wave is done with the previous pair,
-      // whose four ring slots the requests below refill.
+    // One half: the matrix stage's operands (K of tile slot_k, V of tile slot_v) requested from LDS, the
+    // softmax of the current tile on the vector ALU while they arrive, one wait, then the matrix stage
+    // (scores of the next tile, P V of the previous one) with the wave's share of two tile requests inside.
+    auto half = [&](auto slot_k, auto slot_v, const f32x4(&sc0)[NB], const f32x4(&sc1)[NB], bf16x8(&Pc)[NB],
+                    f32x4(&sn0)[NB], f32x4(&sn1)[NB], const bf16x8(&Pp)[NB], auto dma_k_slot, auto dma_v_slot) {
+      uint4 kop[2 * KS], vop[NL];
+      read_k(decltype(slot_k)::value, kop);
+      read_v(decltype(slot_v)::value, vop, 0, NL);
+      __builtin_amdgcn_sched_barrier(0);
+      softmax(sc0, sc1, Pc);
+      pin_p(Pc);
+      mfma_phase_begin();
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): every operand is in, no further waits among the MFMAs
+      request_k(decltype(dma_k_slot)::value);
+      __builtin_amdgcn_sched_barrier(0);
+      qk_mfma(kop, sn0, sn1);
+      request_v(decltype(dma_v_slot)::value);
+      __builtin_amdgcn_sched_barrier(0);
+      pv_mfma(vop, Pp, nullptr);
+      mfma_phase_end();
+      rescale();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // A pair of tiles n, n+1 with n = s (mod 4), s = 1 or 3.  At the barrier K(n+1), K(n+2), V(n-1), V(n)
+    // have landed (everything requested one pair ago) and every wave is done with the previous pair,
+    // whose four ring slots the requests of this pair refill: K(n+3), V(n+1), K(n+4), V(n+2).
+    auto pair = [&](auto s) {
+      constexpr int S0 = decltype(s)::value;
+      using std::integral_constant;
       wait_vmcnt<0>();
       __syncthreads();
-      uint4 kop[2 * KS], vop[NL];
-      // Each half: request the matrix stage's operands from LDS, run the softmax of the current
-      // tile on the vector ALU while they arrive, then the matrix stage with nothing to wait for.
       // odd n: current scores in B, previous P in A
-      read_k(n + 1, kop);
-      read_v(n - 1, vop, 0, NL / 2);
-      __builtin_amdgcn_sched_barrier(0);
-      softmax(sB0, sB1, PB);
-      pin(sB0, sB1, PB);
-      mfma_phase_begin();
-      read_v(n - 1, vop, NL / 2, NL);   // these arrive behind the score MFMAs
-      issue_fast_k(n + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      qk_mfma(kop, sA0, sA1);
-      issue_fast_v(n + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      pv_mfma(vop, PA, nullptr);
-      mfma_phase_end();
-      rescale();
-      __builtin_amdgcn_sched_barrier(0);
-      // even n+1: current scores in A, previous P in B
-      read_k(n + 2, kop);   // for the last pair this is tile n_fast, which the masked loop redoes
-      read_v(n, vop, 0, NL / 2);
-      __builtin_amdgcn_sched_barrier(0);
-      softmax(sA0, sA1, PA);
-      pin(sA0, sA1, PA);
-      mfma_phase_begin();
-      read_v(n, vop, NL / 2, NL);
-      issue_fast_k(n + 4);
-      __builtin_amdgcn_sched_barrier(0);
-      qk_mfma(kop, sB0, sB1);
-      issue_fast_v(n + 2);
-      __builtin_amdgcn_sched_barrier(0);
-      pv_mfma(vop, PB, nullptr);
-      mfma_phase_end();
-      rescale();
-      __builtin_amdgcn_sched_barrier(0);
+      half(integral_constant<int, (S0 + 1) & 3>{}, integral_constant<int, (S0 + 3) & 3>{}, sB0, sB1, PB, sA0, sA1, PA,
+           integral_constant<int, (S0 + 3) & 3>{}, integral_constant<int, (S0 + 1) & 3>{});
+      // even n+1: current scores in A, previous P in B (for the last pair the scores computed here are
+      // those of tile n_fast, which the masked loop redoes)
+      half(integral_constant<int, (S0 + 2) & 3>{}, integral_constant<int, S0 & 3>{}, sA0, sA1, PA, sB0, sB1, PB,
+           integral_constant<int, S0 & 3>{}, integral_constant<int, (S0 + 2) & 3>{});
+    };
+    int n = 1;
+    for (; n + 2 < n_fast; n += 4) {
+      pair(std::integral_constant<int, 1>{});
+      pair(std::integral_constant<int, 3>{});
     }
+    if (n < n_fast) pair(std::integral_constant<int, 1>{});
     // drain: the last P is in A
     wait_vmcnt<0>();
     __syncthreads();
