@@ -73,6 +73,15 @@ def profiled_traffic(fname):
     return None, None
 
 
+def calibrate_copy():
+    """Three 1 GiB device-to-device copies: a kernel of known size to scale rocprofv3's byte counters by."""
+    src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+
+
 def host_threads():
     """(threads the oracle is given, cores the host shows).  A one-GPU machine's share of its host is
     16 cores whatever the machine shows."""
@@ -383,13 +392,6 @@ def bench_decode(args, wname, steps=None, warmup=None, mixed=True, rotate_arenas
         run.step()
         torch.cuda.synchronize()
         cpu, parity = cpu_baseline_and_parity(run, args.seed)
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
     t_step = run.timed(steps, warmup)
     step_events = run.per_step_events(steps)
     t_sep = run.timed(steps, warmup, mode="separate")
@@ -487,6 +489,8 @@ def main():
         import __graft_entry__
         __graft_entry__.build()       # only when nothing is built; otherwise the library is used as it is
     wname = ALIASES.get(args.workload, args.workload)
+    if args.calibrate_copy:
+        calibrate_copy()
     if wname == "sweep":
         from bench_sweep import bench_sweep
         out = bench_sweep(args)
