@@ -75,6 +75,7 @@ def profiled_traffic(fname):
 
 def calibrate_copy():
     """Three 1 GiB device-to-device copies: a kernel of known size to scale rocprofv3's byte counters by."""
+    import torch
     src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
     dst = torch.empty_like(src)
     for _ in range(3):
