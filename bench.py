@@ -54,6 +54,9 @@ def parse():
                     help="with the default workload: skip the extra measurement at 32k context, batch 1")
     ap.add_argument("--no-legs", action="store_true",
                     help="with the default workload: skip the MHA 32k/batch-8 and the chunked-prefill legs")
+    ap.add_argument("--sweep-point", default=None,
+                    choices=["zigzag", "mixed", "all_retrieval", "mixed_by_quantile", "zigzag_by_transport"],
+                    help="with --workload sweep: only this layout's decode at 1k decoded tokens (for a kernel trace)")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--splits", type=int, default=0)
     return ap.parse_args()
@@ -63,11 +66,17 @@ def profiled_traffic(fname):
     """(bytes, source): HBM bytes per launch of the dominant kernel as rocprofv3's FETCH_SIZE /
     WRITE_SIZE counters measured them (two --pmc runs of this program, scaled by a known-size
     copy).  Counters cannot be read from inside the run: the figure comes from the summary
-    kept under profiles/, and the source string says so.  (None, None) without a summary."""
+    kept under profiles/, and the source string names the file and the commit it was measured
+    at.  (None, None) without a summary."""
     try:
+        nbytes, commit = None, "unknown commit"
         for line in open(os.path.join(ROOT, "profiles", fname)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return int(float(line.split(":")[1])), "profiles/%s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)" % fname
+                nbytes = int(float(line.split(":")[1]))
+            elif line.startswith("measured at commit "):
+                commit = line.split()[3]
+        if nbytes is not None:
+            return nbytes, "profiles/%s @ %s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)" % (fname, commit)
     except OSError:
         pass
     return None, None

@@ -142,6 +142,8 @@ def bench_prefill(args, wname, steps=None, warmup=None):
                    sample=f"{n_rows} (query row, head) pairs of the last chunk of one retrieval and one streaming "
                           f"layer, {t_cpu:.2f} s wall on {threads} threads (the host shows {host_cores} cores; a "
                           f"one-GPU box's share is 16), extrapolated by attended (query,key) pairs")
+    import bench as B_
+    traffic, traffic_source = B_.profiled_traffic("prefill_c4_64k_chunked.txt") if wname == "c4_prefill_64k" else (None, None)
     return {
         "metric": "chunked prefill attention TFLOP/s (all layers)", "value": flop / t_step / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": t_step * 1e3,
@@ -159,6 +161,6 @@ def bench_prefill(args, wname, steps=None, warmup=None):
         "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128, 2>, retrieval layer, last 4096-token chunk of 65536 (chunk staging included)",
                      "achieved": flop_last / t_kernel / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_last / t_kernel / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop_per_launch": flop_last,
-                     "avg_launch_us": t_kernel * 1e6, "traffic": None},
+                     "avg_launch_us": t_kernel * 1e6, "traffic": traffic, "traffic_source": traffic_source},
         "cpu_baseline": cpu, "parity_sample": parity,
     }

@@ -73,6 +73,10 @@ def bench_sweep(args):
                                    % (label, mean[i - 1], mean[i], lengths[i - 1], lengths[i], up, down))
         return mean, {"ascending": up, "descending": down}
 
+    point = getattr(args, "sweep_point", None)
+    if point:            # one decode point of one layout (what a kernel trace of a single layout needs)
+        layouts = {point: layouts[point]}
+        decode_lengths = [1024]
     for name, kw in layouts.items():
         st = harness.Stack(L, Hq, Hkv, D, B, max_ctx, S, W, max_chunk=C, **kw)
         view = st.arena.view(torch.bfloat16)
@@ -121,6 +125,13 @@ def bench_sweep(args):
         settle(lambda: decode_time(decode_lengths[0]), name + " decode")
         res["decode_us_per_token"][name], res["decode_us_per_token_both_orders"][name] = \
             both_orders(decode_lengths, decode_time, name + " decode")
+        if point:
+            return {"metric": "per-token decode latency after a 16k prompt and 1k decoded tokens, %s layout" % point,
+                    "value": res["decode_us_per_token"][name][0], "unit": "us/token", "n_gpus": 1, "steps": args.steps,
+                    "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+                    "config": {"workload": "paper_efficiency_sweep, one point", "layout": point, "context": 16384 + 1024,
+                               "sink": S, "window": W, "streaming_heads_per_layer": (
+                                   hmask_q.sum(axis=1).tolist() if point == "mixed_by_quantile" else None)}}
         settle(lambda: prefill_time(prefill_lengths[0]), name + " prefill")
         pre, res["prefill_us_per_token_both_orders"][name] = both_orders(prefill_lengths, lambda T: prefill_time(T) * T, name + " prefill")
         res["prefill_us_per_token"][name] = [t / T for t, T in zip(pre, prefill_lengths)]   # (monotone in total time, reported per token)

@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output into the short tables kept under profiles/.
 
     python -m paper_2508_12407_amd.profile_summary kernels  <dir with *_kernel_trace.csv> [top]
-    python -m paper_2508_12407_amd.profile_summary counters <dir with *_counter_collection.csv> [kernel substring]
+    python -m paper_2508_12407_amd.profile_summary counters <dir with *_counter_collection.csv> [kernel substring[|substring...]]
 
 `kernels`: dispatches grouped by (kernel, grid, workgroup): calls, average / minimum / maximum duration
 in microseconds, share of the GPU time of the run.  `counters`: per (kernel, grid, counter): dispatches,
@@ -36,14 +36,14 @@ def kernels(directory: str, top: int = 12) -> str:
         for r in csv.DictReader(open(path)):
             dur = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
             key = (r["Kernel_Name"], (int(r["Grid_Size_X"]), int(r["Grid_Size_Y"]), int(r["Grid_Size_Z"])), int(r["Workgroup_Size_X"]),
-                   int(r.get("LDS_Block_Size", 0) or 0), int(r.get("VGPR_Count", 0) or 0) + int(r.get("Accum_VGPR_Count", 0) or 0))
+                   int(r.get("LDS_Block_Size", 0) or 0))
             groups[key].append(dur)
     total = sum(sum(v) for v in groups.values())
     rows = sorted(groups.items(), key=lambda kv: -sum(kv[1]))
-    out = ["%-88s %22s %4s %6s %10s %10s %10s %6s %6s %5s" % ("kernel", "grid (threads)", "wg", "calls", "avg_us", "min_us", "max_us", "%time", "lds_B", "regs")]
-    for (name, grid, wg, lds, regs), v in rows[:top]:
-        out.append("%-88s %22s %4d %6d %10.2f %10.2f %10.2f %6.2f %6d %5d" % (short(name), str(grid), wg, len(v), sum(v) / len(v), min(v), max(v),
-                                                                     100 * sum(v) / total, lds, regs))
+    out = ["%-88s %22s %4s %6s %10s %10s %10s %6s %6s" % ("kernel", "grid (threads)", "wg", "calls", "avg_us", "min_us", "max_us", "%time", "lds_B")]
+    for (name, grid, wg, lds), v in rows[:top]:
+        out.append("%-88s %22s %4d %6d %10.2f %10.2f %10.2f %6.2f %6d" % (short(name), str(grid), wg, len(v), sum(v) / len(v), min(v), max(v),
+                                                                   100 * sum(v) / total, lds))
     out.append("GPU time of all dispatches: %.3f ms" % (total / 1e3))
     return "\n".join(out)
 
@@ -52,7 +52,7 @@ def counters(directory: str, only: str = "") -> str:
     groups = collections.defaultdict(list)
     for path in find(directory, "counter_collection.csv"):
         for r in csv.DictReader(open(path)):
-            if only and only not in r["Kernel_Name"]:
+            if only and not any(o in r["Kernel_Name"] for o in only.split("|")):
                 continue
             key = (r["Kernel_Name"], int(r["Grid_Size"]) if "Grid_Size" in r and r["Grid_Size"] else 0, r["Counter_Name"])
             groups[key].append(float(r["Counter_Value"]))
