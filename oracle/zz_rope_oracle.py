@@ -3,9 +3,9 @@
 TEST INFRASTRUCTURE ONLY; shares no code with the HIP path; only tests may import it.
 
 The paper (arXiv 2508.12407) does not mention position encoding; its model (Section 3.1: a
-Llama-3-8B long-context model) uses rotary embeddings, and the survey of this build lists
-"position encoding at append" as an optional step next to the hot path (the paper's point,
-Section 1, is per-layer overhead around attention).  What is computed is the rotary
+Llama-3-8B long-context model) uses rotary embeddings, and encoding K where it is appended
+is a step right next to the hot path (the paper's point, Section 1, is per-layer overhead
+around attention).  What is computed is the rotary
 embedding of Su et al. in the pairing that model family uses: element i of a head vector is
 rotated together with element i + D/2 by the angle of (position, i):
 
