@@ -155,10 +155,10 @@ def bench_prefill(args, wname, steps=None, warmup=None):
         "skipped_tile_fraction": 1.0 - vis / cau,
         "skipped_tile_fraction_by_kind": {"retrieval": 1.0 - kind_counts[False][0] / max(kind_counts[False][1], 1),
                                           "streaming": 1.0 - kind_counts[True][0] / max(kind_counts[True][1], 1)},
-        "tile": "32 keys x 64 query positions x 2 heads (one workgroup's share of a KV tile)",
+        "tile": "32 keys x 64 query positions x 2 heads (the share of a KV tile that four waves work on)",
         # every visited (workgroup, tile) pair is computed in full: scores and P V for 64 x 2 x 32 pairs
         "tile_granular_flop_per_step": vis * 64 * 2 * 32 * 4 * D,
-        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128, 2>, retrieval layer, last 4096-token chunk of 65536 (chunk staging included)",
+        "roofline": {"bound": "mfma", "kernel": "zz_prefill_kernel<128, 2, paired>, retrieval layer, last 4096-token chunk of 65536 (chunk staging included)",
                      "achieved": flop_last / t_kernel / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flop_last / t_kernel / 1e12 / MFMA_BF16_PEAK_TFLOPS, "flop_per_launch": flop_last,
                      "avg_launch_us": t_kernel * 1e6, "traffic": traffic, "traffic_source": traffic_source},

@@ -228,11 +228,11 @@ int64_t zz_slot_of(const zz_config *cfg, int layer, int kv_head, int64_t pos);
  * (element index * 2 = byte offset inside the tile). */
 int64_t zz_kv_elem_offset(const zz_ctx *ctx, int layer, int which, int b, int kv_head, int64_t slot, int d);
 
-/* Pure host arithmetic: how many (workgroup, 32-key tile) visits the next
+/* Pure host arithmetic: how many (group of four waves, 32-key tile) visits the next
  * zz_attn_prefill(layer, n_new) performs, and how many a kernel that skipped
  * nothing below the causal diagonal would perform at the same granularity
- * (a workgroup covers 64 consecutive query positions for even group sizes and 128 for odd
- * ones).  1 - visited/causal is the skipped-tile
+ * (four waves - a workgroup, or half of an eight-wave one - cover 64 consecutive query
+ * positions for even group sizes and 128 for odd ones).  1 - visited/causal is the skipped-tile
  * fraction that the sink + window mask of streaming heads allows (Section 3.3). */
 int zz_prefill_tile_counts(const zz_ctx *ctx, int layer, int n_new, int64_t *visited, int64_t *causal);
 
@@ -267,7 +267,9 @@ const char *zz_last_error_detail(void);
 enum {
   ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 1)  */
   ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
-  ZZ_TUNE_NUM_CU = 3             /* override the detected compute-unit count               */
+  ZZ_TUNE_NUM_CU = 3,            /* override the detected compute-unit count               */
+  ZZ_TUNE_PREFILL_PAIRING = 4    /* 1 (default): prefill runs two head chunks of a KV head in
+                                    one eight-wave workgroup where the shape allows; 0: never */
 };
 int zz_tune(zz_ctx *ctx, int key, int value);
 

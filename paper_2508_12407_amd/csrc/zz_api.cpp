@@ -135,6 +135,7 @@ struct zz_ctx {
   // them the latency every workgroup pays for its first tile and for its merge.
   int tune_wg_per_cu = 1;
   int tune_splits = 0;
+  int tune_prefill_pairing = 1;
   // The split counters live in caller memory that the library has never seen: every decode call
   // enqueues a small clear ahead of its attention launch until one such clear has been issued on
   // a stream that is not being captured (a clear recorded into a graph only runs when the graph
@@ -433,6 +434,10 @@ int zz_tune(zz_ctx *ctx, int key, int value) {
       if (value < 1 || value > 4096) return ZZ_ERANGE;
       ctx->num_cu = value;
       return ZZ_OK;
+    case ZZ_TUNE_PREFILL_PAIRING:
+      if (value < 0 || value > 1) return ZZ_ERANGE;
+      ctx->tune_prefill_pairing = value;
+      return ZZ_OK;
     default:
       return ZZ_EINVAL;
   }
@@ -543,7 +548,7 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
     p.sink = c.sink;
     p.window = c.window;
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    if (hipError_t e = zz_launch_prefill(p, lens, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+    if (hipError_t e = zz_launch_prefill(p, lens, ctx->tune_prefill_pairing != 0, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
   }
   return ZZ_OK;
 }

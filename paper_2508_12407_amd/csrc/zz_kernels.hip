@@ -684,19 +684,31 @@ __device__ __forceinline__ float max_over_kg(float v) {
 
 #define ZZ_RESCALE_THRESHOLD 8.0f  // in log2 units
 
-template <int D, int NB>
-__global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, zz_seq_lens sl, int Gc) {
+// PAIRED: two such groups of four waves in one workgroup, on two head chunks of the same KV head and the
+// same query positions.  They share the K/V ring (each tile is requested once for both) and, in the
+// pipelined loop, run half an iteration apart: every SIMD holds one wave of each group, and while one
+// group is in its matrix stage the other is in its softmax stage, held there by workgroup barriers
+// between the stages.  (Two independent workgroups per compute unit fall into step with each other
+// instead: both in the matrix stage, then both in the softmax stage, with the matrix pipe idle.)
+template <int D, int NB, bool PAIRED>
+__global__ __launch_bounds__(PAIRED ? 512 : 256, PAIRED ? 1 : ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(zz_prefill_params p, zz_seq_lens sl, int Gc) {
   constexpr int KS = D / 32, NL = D / 16, HALF_U4 = 4 * D, TILE_U4 = 8 * D;
-  constexpr int CPW = NL / ZZ_WAVES_PER_WG;  // 1 KiB chunks of a K part (or V part) each wave brings in
+  constexpr int RING_WAVES = PAIRED ? 2 * ZZ_WAVES_PER_WG : ZZ_WAVES_PER_WG;   // waves that fill the ring together
+  constexpr int CPW = NL / RING_WAVES;  // 1 KiB chunks of a K part (or V part) each wave brings in
+  static_assert(CPW >= 1 && CPW * RING_WAVES == NL, "a part's chunks divide evenly over the waves");
   constexpr int RING = 4;  // power of two: the slot of tile n is n & 3
   __shared__ uint4 s_k[RING][HALF_U4];
   __shared__ uint4 s_v[RING][HALF_U4];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int ring_wave = threadIdx.x >> 6;             // the wave's place among those that fill the ring
+  const int wave = ring_wave & (ZZ_WAVES_PER_WG - 1);   // ... among the four that share its query block
+  const int pair_group = ring_wave / ZZ_WAVES_PER_WG;   // 0, or 1 for the second group of a paired workgroup
   const int col = lane & 15, kg = lane >> 4;
   const int G = p.group_size;
   const int n_hchunks = G / Gc;
-  const int hg = blockIdx.y / n_hchunks, hc = blockIdx.y % n_hchunks;
+  const int ny = PAIRED ? n_hchunks / 2 : n_hchunks;    // workgroups per KV head along y
+  const int hg = blockIdx.y / ny, hc = PAIRED ? 2 * (blockIdx.y % ny) + pair_group : blockIdx.y % ny;
   const int b = blockIdx.z;
   const int n_past = sl.ragged ? (int)sl.len[b] : p.n_past;   // tokens this sequence holds already
   const int g = p.heads[hg];
@@ -760,9 +772,9 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
   };
   // Requests for the K part / V part of the n-th tile of the sequence into ring slot n & 3.
   // Each wave brings CPW KiB-chunks of the part; the tile address stays in scalar registers.
-  const unsigned lane_off = (unsigned)(wave * CPW * 64 + lane) * 16u;
-  const unsigned lds_k0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_k[0][wave * CPW * 64]);
-  const unsigned lds_v0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_v[0][wave * CPW * 64]);
+  const unsigned lane_off = (unsigned)(ring_wave * CPW * 64 + lane) * 16u;
+  const unsigned lds_k0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_k[0][ring_wave * CPW * 64]);
+  const unsigned lds_v0 = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(lds_void *)&s_v[0][ring_wave * CPW * 64]);
   auto issue_k = [&](int n) {
     int ct, sk;
     const uint4 *src = tile_src(n, ct, sk);
@@ -1041,6 +1053,81 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
     auto request_v = [&](int slot) {
       dma_to_lds<CPW>(next_tile(pvv) + HALF_U4 * 16, lane_off, lds_v0 + (unsigned)slot * (HALF_U4 * 16));
     };
+    if constexpr (PAIRED) {
+      // Both groups in step through the first two tiles.  Requests go out in the order the loop continues them
+      // (per tile n: V(n+1), then K(n+4)):  K(0) K(1) K(2) V(0) K(3) V(1), then K(4) once K(0) has been read.
+      auto wg_barrier = [&]() { asm volatile("s_barrier" ::: "memory"); };
+      request_k(0);
+      request_k(1);
+      request_k(2);
+      request_v(0);
+      request_k(3);
+      request_v(1);
+      wait_vmcnt<5 * CPW>();  // K(0)
+      wg_barrier();
+      qk(0, sA0, sA1);
+      wait_vmcnt<4 * CPW>();  // K(1)
+      wg_barrier();           // ... and every wave has read K(0)
+      request_k(0);           // K(4)
+      qk(1, sB0, sB1);
+      softmax(sA0, sA1, PA);
+      rescale();
+      pin(sB0, sB1, PA);
+      wait_vmcnt<3 * CPW>();  // K(2), V(0)
+      wg_barrier();
+      if (pair_group == 1) wg_barrier();   // the second group runs one stage behind the first from here on
+      // One tile n of a group.  [softmax stage] V(n+1) and K(n+4) requested, the K operands of tile n+1 read
+      // from LDS while the softmax of tile n runs; wait for them and for this wave's share of K(n+2), which
+      // everyone reads two stages on; barrier.  [matrix stage] the V operands of tile n-1 read from LDS while
+      // the scores of tile n+1 are computed, then P V of tile n-1; wait for this wave's share of V(n), which
+      // everyone reads in the matrix stage after next; barrier.  With the first group in stage 2n and the
+      // second in 2n+1 for the softmax of tile n: K(j) is last read in stage 2j-1 and its slot refilled (by
+      // K(j+4)) from stage 2j on; V(j) is last read in stage 2j+4 and its slot refilled (by V(j+4)) from
+      // stage 2j+6 on.
+      auto half = [&](auto slot_k, auto slot_v, const f32x4(&sc0)[NB], const f32x4(&sc1)[NB], bf16x8(&Pc)[NB],
+                      f32x4(&sn0)[NB], f32x4(&sn1)[NB], const bf16x8(&Pp)[NB], auto dma_k_slot, auto dma_v_slot) {
+        uint4 kop[2 * KS], vop[NL];
+        request_v(decltype(dma_v_slot)::value);
+        request_k(decltype(dma_k_slot)::value);
+        read_k(decltype(slot_k)::value, kop);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax(sc0, sc1, Pc);
+        pin_p(Pc);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): the K operands are in registers
+        wait_vmcnt<4 * CPW>();                // K(n+2); later: V(n), K(n+3), V(n+1), K(n+4)
+        wg_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(decltype(slot_v)::value, vop, 0, NL);
+        __builtin_amdgcn_sched_barrier(0);
+        qk_mfma(kop, sn0, sn1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // the V operands are in registers
+        pv_mfma(vop, Pp, nullptr);
+        __builtin_amdgcn_sched_barrier(0);
+        rescale();
+        wait_vmcnt<3 * CPW>();                // V(n); later: K(n+3), V(n+1), K(n+4)
+        wg_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      auto pair = [&](auto s) {
+        constexpr int S0 = decltype(s)::value;
+        using std::integral_constant;
+        // odd n = S0 (mod 4): current scores in B, previous P in A; K(n+4) goes to slot n, V(n+1) to slot n+1
+        half(integral_constant<int, (S0 + 1) & 3>{}, integral_constant<int, (S0 + 3) & 3>{}, sB0, sB1, PB, sA0, sA1, PA,
+             integral_constant<int, S0 & 3>{}, integral_constant<int, (S0 + 1) & 3>{});
+        // even n+1
+        half(integral_constant<int, (S0 + 2) & 3>{}, integral_constant<int, S0 & 3>{}, sA0, sA1, PA, sB0, sB1, PB,
+             integral_constant<int, (S0 + 1) & 3>{}, integral_constant<int, (S0 + 2) & 3>{});
+      };
+      int n = 1;
+      for (; n + 2 < n_fast; n += 4) {
+        pair(std::integral_constant<int, 1>{});
+        pair(std::integral_constant<int, 3>{});
+      }
+      if (n < n_fast) pair(std::integral_constant<int, 1>{});
+      if (pair_group == 0) wg_barrier();   // the first group waits for the second group's last stage
+    } else {
     request_k(0);
     request_k(1);
     wait_vmcnt<CPW>();  // K(0)
@@ -1102,6 +1189,7 @@ __global__ __launch_bounds__(256, ZZ_PREFILL_WG_PER_CU) void zz_prefill_kernel(z
       pair(std::integral_constant<int, 3>{});
     }
     if (n < n_fast) pair(std::integral_constant<int, 1>{});
+    }
     // drain: the last P is in A
     wait_vmcnt<0>();
     __syncthreads();
@@ -1335,12 +1423,16 @@ hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, 
   return launch(zz_probe_read_kernel<false>, dim3(n_wg), dim3(256), s, (const uint4 *)buf, n_blocks, (uint4 *)sink);
 }
 
-hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, hipStream_t s) {
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, bool pairing, hipStream_t s) {
   constexpr int NB = ZZ_PREFILL_NB;
   const int G = p.group_size;
   const int Gc = zz_prefill_heads_per_wave(G);  // heads per wave, divides NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
-  const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * (G / Gc), p.batch);
-  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB>, grid, dim3(256), s, p, lens, Gc);
-  return launch(zz_prefill_kernel<64, NB>, grid, dim3(256), s, p, lens, Gc);
+  const int n_hchunks = G / Gc;
+  const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * n_hchunks, p.batch);
+  // two head chunks of a KV head in one workgroup of eight waves where the head count allows it
+  if (pairing && p.head_dim == 128 && n_hchunks % 2 == 0)
+    return launch(zz_prefill_kernel<128, NB, true>, dim3(grid.x, grid.y / 2, grid.z), dim3(512), s, p, lens, Gc);
+  if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB, false>, grid, dim3(256), s, p, lens, Gc);
+  return launch(zz_prefill_kernel<64, NB, false>, grid, dim3(256), s, p, lens, Gc);
 }

@@ -333,6 +333,35 @@ def test_prefill_llama_shape_chunked_ragged(streaming):
     run_prefill_case(1, 32, 8, 128, 64, 256, 1500, [0, 7, 450, 451, 963, 1500], 5, streaming)
 
 
+@pytest.mark.parametrize("streaming", [False, True])
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (16, 2), (32, 2)])
+def test_prefill_eight_wave_and_four_wave_forms_agree_bit_for_bit(streaming, Hq, Hkv):
+    """Where a KV head has an even number of head chunks (group sizes 4, 8, 16 at D = 128) the prefill
+    launch puts two of them into one workgroup of eight waves that share the K/V ring and alternate
+    stages; ZZ_TUNE_PREFILL_PAIRING = 0 keeps one chunk per four-wave workgroup.  Every wave does the
+    same arithmetic on the same tiles in both forms, so the outputs must be equal bit for bit - across
+    chunk sizes that give the pipelined loop 0, 1, 3 and many tiles, ragged tails and a chunk of one."""
+    H, zb = _harness()
+    B, D, S, W, T = 2, 128, 64, 256, 2400
+    chunks = [0, 1, 70, 200, 328, 1100, 1101, 2400]
+    q, k, v = zz_inputs.make_qkv(23, B, T, Hq, Hkv, D)
+    qd, kd, vd = H.to_dev_bf16(q), H.to_dev_bf16(k), H.to_dev_bf16(v)
+    outs = {}
+    for pairing in (1, 0):
+        st = H.Stack(1, Hq, Hkv, D, B, T, S, W, max_chunk=1300, layer_is_streaming=[int(streaming)], poison_arena=True)
+        st.ctx.tune(zb.TUNE_PREFILL_PAIRING, pairing)
+        got = []
+        for a, b in zip(chunks[:-1], chunks[1:]):
+            qa, ka, va = qd[:, a:b].contiguous(), kd[:, a:b].contiguous(), vd[:, a:b].contiguous()
+            got.append(st.prefill(0, qa, ka, va).clone())
+            st.append(0, ka, va)
+        outs[pairing] = torch.cat(got, dim=1)
+        del st
+    assert torch.equal(outs[1].view(torch.int16), outs[0].view(torch.int16))
+    want = O.attention(q, k, v, kinds_of(streaming, Hkv), S, W)
+    check(H.from_dev(outs[0]), want, ("four-wave form", streaming, Hq, Hkv))
+
+
 @pytest.mark.parametrize("Hq,Hkv,D", [(4, 4, 128), (2, 1, 64), (16, 2, 128), (32, 2, 64), (6, 2, 64)])
 def test_prefill_group_sizes(Hq, Hkv, D):
     for streaming in (False, True):
