@@ -74,7 +74,7 @@ def profiled_traffic(fname):
             if line.startswith("traffic_bytes_per_launch:"):
                 nbytes = int(float(line.split(":")[1]))
             elif line.startswith("measured at commit "):
-                commit = line.split()[3]
+                commit = line.split()[3].rstrip(";,.")
         if nbytes is not None:
             return nbytes, "profiles/%s @ %s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)" % (fname, commit)
     except OSError:
