@@ -269,7 +269,9 @@ enum {
   ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
   ZZ_TUNE_NUM_CU = 3,            /* override the detected compute-unit count               */
   ZZ_TUNE_PREFILL_PAIRING = 4    /* 1 (default): prefill runs two head chunks of a KV head in
-                                    one eight-wave workgroup where the shape allows; 0: never */
+                                    one eight-wave workgroup where the shape allows, the launch
+                                    keeps a workgroup per compute unit and the cache already holds
+                                    at least a chunk; 0: never; 2: wherever the shape allows */
 };
 int zz_tune(zz_ctx *ctx, int key, int value);
 

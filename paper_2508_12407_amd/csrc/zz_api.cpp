@@ -435,7 +435,7 @@ int zz_tune(zz_ctx *ctx, int key, int value) {
       ctx->num_cu = value;
       return ZZ_OK;
     case ZZ_TUNE_PREFILL_PAIRING:
-      if (value < 0 || value > 1) return ZZ_ERANGE;
+      if (value < 0 || value > 2) return ZZ_ERANGE;
       ctx->tune_prefill_pairing = value;
       return ZZ_OK;
     default:
@@ -548,7 +548,7 @@ int prefill_run(zz_ctx *ctx, const Layer &L, int b0, int nb, int64_t n_past, con
     p.sink = c.sink;
     p.window = c.window;
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    if (hipError_t e = zz_launch_prefill(p, lens, ctx->tune_prefill_pairing != 0, (hipStream_t)stream)) return hip_failed("prefill kernel", e);
+    if (hipError_t e = zz_launch_prefill(p, lens, ctx->tune_prefill_pairing == 0 ? -1 : ctx->tune_prefill_pairing == 2 ? 0 : num_cu(ctx), (hipStream_t)stream)) return hip_failed("prefill kernel", e);
   }
   return ZZ_OK;
 }

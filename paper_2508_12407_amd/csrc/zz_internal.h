@@ -114,8 +114,9 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t s);
 hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t s);
 hipError_t zz_launch_zero(int *p, int n, hipStream_t s);
 hipError_t zz_launch_stage(const zz_stage_params &p, const zz_seq_lens &lens, hipStream_t s);
-// pairing: allow the eight-wave form (two head chunks of a KV head per workgroup) where the shape permits it
-hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, bool pairing, hipStream_t s);
+// pair_min_wg: the eight-wave form (two head chunks of a KV head per workgroup) is used where the shape permits
+// it and the launch then has at least that many workgroups; negative: never
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, int pair_min_wg, hipStream_t s);
 hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, int n_wg, void *sink, hipStream_t s);
 int zz_query_num_cu();  // compute units of the current device, or 0 if none is usable
 // Device address, on the current device, of the library's own static scratch array

@@ -1423,15 +1423,24 @@ hipError_t zz_launch_probe_read(const void *buf, size_t bytes, int nontemporal, 
   return launch(zz_probe_read_kernel<false>, dim3(n_wg), dim3(256), s, (const uint4 *)buf, n_blocks, (uint4 *)sink);
 }
 
-hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, bool pairing, hipStream_t s) {
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, int pair_min_wg, hipStream_t s) {
   constexpr int NB = ZZ_PREFILL_NB;
   const int G = p.group_size;
   const int Gc = zz_prefill_heads_per_wave(G);  // heads per wave, divides NB
   const int qw = 16 * (NB / Gc) * ZZ_WAVES_PER_WG;        // query positions per workgroup
   const int n_hchunks = G / Gc;
   const dim3 grid((p.n_new + qw - 1) / qw, p.grp.n_heads * n_hchunks, p.batch);
-  // two head chunks of a KV head in one workgroup of eight waves where the head count allows it
-  if (pairing && p.head_dim == 128 && n_hchunks % 2 == 0)
+  // Two head chunks of a KV head in one workgroup of eight waves where the head count allows it and the
+  // launch still has a workgroup for every compute unit that way (a 1k-token chunk at batch 1 has not: the
+  // four-wave form then spreads over twice as many units and is the faster one).  pair_min_wg = 0: always.
+  // (Nor does it pay on a chunk with little behind it, where most tiles are diagonal ones outside the
+  // pipelined loop: 4 % slower on the first 4096-token chunk of a prompt, equal on the second, faster after.)
+  const int64_t paired_wgs = (int64_t)grid.x * (grid.y / 2) * grid.z;
+  int64_t longest_past = p.n_past;
+  if (lens.ragged)
+    for (int b = 0; b < p.batch; ++b) longest_past = lens.len[b] > longest_past ? (int64_t)lens.len[b] : longest_past;
+  const bool worth = pair_min_wg == 0 || (paired_wgs >= pair_min_wg && longest_past >= p.n_new);
+  if (pair_min_wg >= 0 && p.head_dim == 128 && n_hchunks % 2 == 0 && worth)
     return launch(zz_prefill_kernel<128, NB, true>, dim3(grid.x, grid.y / 2, grid.z), dim3(512), s, p, lens, Gc);
   if (p.head_dim == 128) return launch(zz_prefill_kernel<128, NB, false>, grid, dim3(256), s, p, lens, Gc);
   return launch(zz_prefill_kernel<64, NB, false>, grid, dim3(256), s, p, lens, Gc);

@@ -48,7 +48,7 @@ hipError_t zz_launch_stage(const zz_stage_params &p, const zz_seq_lens &, hipStr
   EXPECT(p.n_new > 0 && (p.n_new + 31) / 32 <= p.stage_tiles);
   return hipSuccess;
 }
-hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, bool, hipStream_t) {
+hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens, int, hipStream_t) {
   ++g_launches;
   ++g_prefill_launches;
   EXPECT(!lens.ragged || p.batch <= ZZ_MAX_RAGGED_BATCH);
