@@ -268,6 +268,10 @@ enum {
   ZZ_TUNE_DECODE_WG_PER_CU = 1,  /* target decode workgroups per compute unit (default 1)  */
   ZZ_TUNE_DECODE_SPLITS = 2,     /* force the split count (0 = automatic)                  */
   ZZ_TUNE_NUM_CU = 3,            /* override the detected compute-unit count               */
+  ZZ_TUNE_DECODE_XCD_SKEW = 5,   /* in 1/1000 of a split: how much longer the range of a decode split
+                                    that lands on an even XCD is, and its odd neighbour's shorter
+                                    (default 50, applied to splits of 128 tiles or more; a value
+                                    set here applies to splits of any length; 0: even ranges) */
   ZZ_TUNE_PREFILL_PAIRING = 4    /* 1 (default): prefill runs two head chunks of a KV head in
                                     one eight-wave workgroup where the shape allows, the launch
                                     keeps a workgroup per compute unit and the cache already holds

@@ -16,7 +16,7 @@ ZZ_TILE_SLOTS = 32
 ZZ_MAX_SPLITS = 128
 ZZ_MAX_RAGGED_BATCH = 256
 ERR = dict(OK=0, EINVAL=-1, ERANGE=-2, ENOSPC=-3, EALIGN=-4, ESTATE=-5, EUNSUPPORTED=-6, EHIP=-7)
-TUNE_DECODE_WG_PER_CU, TUNE_DECODE_SPLITS, TUNE_NUM_CU, TUNE_PREFILL_PAIRING = 1, 2, 3, 4
+TUNE_DECODE_WG_PER_CU, TUNE_DECODE_SPLITS, TUNE_NUM_CU, TUNE_PREFILL_PAIRING, TUNE_DECODE_XCD_SKEW = 1, 2, 3, 4, 5
 
 
 class ZzConfig(C.Structure):

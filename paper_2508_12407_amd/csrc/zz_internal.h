@@ -66,6 +66,7 @@ struct zz_decode_params {
   int32_t n_valid;                // occupied slots (prefix of the cache)
   int32_t n_tiles_valid;          // ceil(n_valid / 32)
   int32_t tiles_per_split, n_splits;
+  int32_t tile_skew;              // tiles a split on an even XCD takes more, its odd neighbour fewer (0: even ranges)
   int32_t batch, n_q_heads, n_kv_heads, head_dim, group_size;
   float scale_log2e;              // softmax scale * log2(e)
   uint32_t *debug_word;           // as in zz_append_params (the fused append writes a slot too)

@@ -78,7 +78,7 @@ def test_append_cache_is_bit_exact(D, pattern):
 # ---------------------------------------------------------------------------
 
 def run_decode_case(B, Hq, Hkv, D, S, W, T, seed, streaming, q_gain=1.0, splits=None, one_by_one_tail=0,
-                    layout_mixed=None):
+                    layout_mixed=None, skew=None):
     """Fill a 1-layer cache with T tokens, decode the newest position, compare."""
     H, zb = _harness()
     q, k, v = zz_inputs.make_qkv(seed, B, T, Hq, Hkv, D, q_gain=q_gain)
@@ -91,6 +91,8 @@ def run_decode_case(B, Hq, Hkv, D, S, W, T, seed, streaming, q_gain=1.0, splits=
         kinds = np.asarray(layout_mixed, bool)
     if splits is not None:
         st.ctx.tune(zb.TUNE_DECODE_SPLITS, splits)
+    if skew is not None:
+        st.ctx.tune(zb.TUNE_DECODE_XCD_SKEW, skew)
     kd, vd = H.to_dev_bf16(k), H.to_dev_bf16(v)
     bulk = T - one_by_one_tail
     if bulk:
@@ -114,6 +116,28 @@ def test_decode_tiny_shape_every_length(streaming, T):
 def test_decode_llama_shape_ragged_tail_across_split_counts(streaming, splits):
     # 3333 tokens = 104 full tiles + 5 slots; several tiles per wave and a ragged tail
     run_decode_case(2, 32, 8, 128, 64, 256, 3333, 7, streaming, splits=splits)
+
+
+@pytest.mark.parametrize("splits", [2, 3, 7, 8, 33])
+@pytest.mark.parametrize("skew", [50, 200])
+def test_decode_uneven_split_ranges_cover_the_cache_exactly_once(splits, skew):
+    """Neighbouring splits may share their two ranges unevenly (the split on an even XCD takes more tiles): odd
+    and even split counts, a last split shorter than the others, skews of 5 % and 20 % of a split, odd and
+    even numbers of (head, sequence) units before a unit (which decides which neighbour is the long one), a
+    ragged last tile, and the fused append landing in a lengthened or a shortened range."""
+    for B, T in ((2, 3333), (3, 2048 + 17)):
+        run_decode_case(B, 32, 8, 128, 64, 256, T, 70 + splits, False, splits=splits, skew=skew)
+    H, zb = _harness()
+    B, Hq, Hkv, D, S, W, T = 3, 8, 2, 128, 64, 256, 1500
+    q, k, v = zz_inputs.make_qkv(71, B, T + 40, Hq, Hkv, D)
+    st = H.Stack(1, Hq, Hkv, D, B, T + 48, S, W, layer_is_streaming=[0], poison_arena=True)
+    st.ctx.tune(zb.TUNE_DECODE_SPLITS, splits)
+    st.ctx.tune(zb.TUNE_DECODE_XCD_SKEW, skew)
+    kd, vd = H.to_dev_bf16(k), H.to_dev_bf16(v)
+    st.append(0, kd[:, :T].contiguous(), vd[:, :T].contiguous())
+    for t in range(T, T + 40):
+        got = H.from_dev(st.decode_step(0, H.to_dev_bf16(q[:, t]), kd[:, t:t + 1].contiguous(), vd[:, t:t + 1].contiguous()))
+        check(got, O.decode_row(q[:, t], k, v, t, kinds_of(False, Hkv), S, W), ("uneven ranges, fused append", splits, skew, t))
 
 
 def test_decode_split_merge_is_race_free_with_far_more_workgroups_than_cus():
