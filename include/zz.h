@@ -273,9 +273,10 @@ enum {
                                     (default 50, applied to splits of 128 tiles or more; a value
                                     set here applies to splits of any length; 0: even ranges) */
   ZZ_TUNE_PREFILL_PAIRING = 4    /* 1 (default): prefill runs two head chunks of a KV head in
-                                    one eight-wave workgroup where the shape allows, the launch
-                                    keeps a workgroup per compute unit and the cache already holds
-                                    at least a chunk; 0: never; 2: wherever the shape allows */
+                                    one eight-wave workgroup where the shape allows, for retrieval
+                                    heads, if the launch keeps a workgroup per compute unit and the
+                                    cache already holds at least a chunk; 0: never; 2: wherever
+                                    the shape allows */
 };
 int zz_tune(zz_ctx *ctx, int key, int value);
 
