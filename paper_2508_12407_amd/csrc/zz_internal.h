@@ -74,6 +74,37 @@ struct zz_decode_params {
   int32_t new_pos;                // position of the newest token (its row of the tables)
 };
 
+// The range of tiles [t0, t1) of split `split` of a unit with n_tiles tiles in n_splits splits of
+// tiles_per_split.  With tile_skew > 0 the two splits of a pair (2k, 2k+1) share their 2 * tiles_per_split
+// tiles unevenly: the one whose workgroup has an even linear index (first_parity: parity of the index of the
+// workgroup with split 0) takes tile_skew more, the other as many fewer; an unpaired last split keeps its
+// plain range.  The ranges of splits 0 .. n_splits-1 tile [0, n_tiles) exactly once, none empty, provided
+// (n_splits-1) * tiles_per_split < n_tiles <= n_splits * tiles_per_split and the last split's plain length
+// exceeds tile_skew: what the host guarantees (plan_decode, decode_tile_skew) and its test harness checks
+// for every launch and, on its own, over all small cases.  Used by the kernel and by the host's checks.
+#if defined(__HIPCC__) || defined(__CUDACC__)
+#define ZZ_HOST_DEVICE __host__ __device__
+#else
+#define ZZ_HOST_DEVICE
+#endif
+ZZ_HOST_DEVICE inline void zz_split_range(int split, int n_splits, int tiles_per_split, int tile_skew, int first_parity,
+                                          int n_tiles, int *t0, int *t1) {
+  int a = split * tiles_per_split, b = a + tiles_per_split;
+  if (tile_skew > 0) {
+    const int base = (split & ~1) * tiles_per_split;
+    const int first_len = tiles_per_split + ((first_parity & 1) == 0 ? tile_skew : -tile_skew);
+    if (split & 1) {
+      a = base + first_len;
+      b = base + 2 * tiles_per_split;
+    } else if (split + 1 < n_splits) {
+      a = base;
+      b = base + first_len;
+    }
+  }
+  *t0 = a;
+  *t1 = b < n_tiles ? b : n_tiles;
+}
+
 // Decode over sequences of different lengths: the workgroups of all sequences form one
 // flat grid dimension, sequence b owning workgroups [first_wg[b], first_wg[b+1]); every
 // per-sequence quantity (occupied slots, slot of the newest token) follows from seq_len[b].

@@ -285,20 +285,9 @@ __device__ __forceinline__ void decode_body(const zz_decode_params &p, const int
   // 6 % faster than the odd ones (measured; the launch ends with its slowest workgroup), so the split that
   // lands on an even XCD takes tile_skew tiles more and its neighbour as many fewer.  A wrong guess of the
   // placement costs time, never correctness: the ranges still tile the cache exactly once.
-  int t0 = split * p.tiles_per_split, t1 = t0 + p.tiles_per_split;
-  if (p.tile_skew > 0) {
-    const int first_parity = (int)(gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) & 1;   // XCD parity of split 0 of this unit
-    const int base = (split & ~1) * p.tiles_per_split;
-    const int first_len = p.tiles_per_split + (first_parity == 0 ? p.tile_skew : -p.tile_skew);
-    if (split & 1) {
-      t0 = base + first_len;
-      t1 = base + 2 * p.tiles_per_split;
-    } else if (split + 1 < n_splits) {
-      t0 = base;
-      t1 = base + first_len;
-    }
-  }
-  t1 = min(t1, n_tiles_valid);
+  int t0, t1;
+  zz_split_range(split, n_splits, p.tiles_per_split, p.tile_skew,
+                 (int)(gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)) & 1, n_tiles_valid, &t0, &t1);
   const int last_tile = n_tiles_valid - 1;
   const bool partial_tail = (n_valid & 31) != 0;
 

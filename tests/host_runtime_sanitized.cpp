@@ -58,6 +58,7 @@ hipError_t zz_launch_prefill(const zz_prefill_params &p, const zz_seq_lens &lens
   EXPECT(((int64_t)p.n_past + 31) / 32 <= p.grp.n_tiles || p.grp.streaming);
   return hipSuccess;
 }
+static int g_skewed_launches = 0;
 hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t) {
   ++g_launches;
   EXPECT(p.n_splits >= 1 && p.n_splits <= ZZ_MAX_SPLITS && p.tiles_per_split >= 1);
@@ -66,6 +67,19 @@ hipError_t zz_launch_decode(const zz_decode_params &p, hipStream_t) {
   EXPECT((int64_t)p.n_splits * p.tiles_per_split >= p.n_tiles_valid);        // every tile covered
   EXPECT(p.new_slot < p.n_valid);
   EXPECT(p.batch <= 65535 && p.grp.n_heads <= 65535);
+  // the ranges the kernel will derive tile the cache exactly once, whichever parity a unit starts on
+  EXPECT(p.tile_skew >= 0 && p.tile_skew < p.tiles_per_split);
+  for (int parity = 0; parity < 2; ++parity) {
+    int next = 0;
+    for (int s = 0; s < p.n_splits; ++s) {
+      int t0, t1;
+      zz_split_range(s, p.n_splits, p.tiles_per_split, p.tile_skew, parity, p.n_tiles_valid, &t0, &t1);
+      EXPECT(t0 == next && t1 > t0);
+      next = t1;
+    }
+    EXPECT(next == p.n_tiles_valid);
+  }
+  if (p.tile_skew > 0) ++g_skewed_launches;
   return hipSuccess;
 }
 hipError_t zz_launch_decode_ragged(const zz_decode_ragged_params &p, int total_wg, hipStream_t) {
@@ -145,6 +159,40 @@ static int time_decode_calls() {
 int main(int argc, char **argv) {
   if (argc > 1 && std::strcmp(argv[1], "--time") == 0) return time_decode_calls();
   void *T = (void *)0x30000000;  // fake, aligned tensor address: the recorders never touch it
+  // 0. the split ranges on their own: every (tiles per split, split count, length of the last split, skew,
+  // parity) up to 12 tiles per split and 9 splits, under the conditions the host promises the kernel
+  for (int tps = 1; tps <= 12; ++tps)
+    for (int ns = 1; ns <= 9; ++ns)
+      for (int last = 1; last <= tps; ++last)
+        for (int skew = 0; skew < last && skew < tps; ++skew)
+          for (int parity = 0; parity < 2; ++parity) {
+            const int n_tiles = (ns - 1) * tps + last;
+            int next = 0;
+            for (int s = 0; s < ns; ++s) {
+              int t0, t1;
+              zz_split_range(s, ns, tps, skew, parity, n_tiles, &t0, &t1);
+              EXPECT(t0 == next && t1 > t0);
+              if (skew == 0) EXPECT(t0 == s * tps);
+              next = t1;
+            }
+            EXPECT(next == n_tiles);
+          }
+  // 0b. decode calls with explicit skews, split counts and lengths: the launch recorder checks each plan
+  {
+    zz_ctx *ctx = make(2, 32, 8, 128, 3, 40000, 64, 256, 0, ZZ_ZIGZAG, {0, 1}, {});
+    for (int skew : {0, 50, 200})
+      for (int splits : {0, 2, 3, 7, 8, 33, 128})
+        for (int64_t n : {1, 100, 1023, 1024, 3333, 20000, 39998}) {
+          EXPECT(zz_tune(ctx, ZZ_TUNE_DECODE_XCD_SKEW, skew) == ZZ_OK);
+          EXPECT(zz_tune(ctx, ZZ_TUNE_DECODE_SPLITS, splits) == ZZ_OK);
+          EXPECT(zz_set_layer_len(ctx, 0, n) == ZZ_OK);
+          EXPECT(zz_decode_step(ctx, 0, T, T, T, T, nullptr) == ZZ_OK);
+          EXPECT(zz_attn_decode(ctx, 0, T, T, nullptr) == ZZ_OK);
+        }
+    EXPECT(g_skewed_launches > 20);
+    EXPECT(zz_tune(ctx, ZZ_TUNE_DECODE_XCD_SKEW, 201) == ZZ_ERANGE);
+    zz_destroy(ctx);
+  }
   // 1. zigzag stack, equal lengths: append / prefill / decode at many lengths and split settings
   {
     zz_ctx *ctx = make(4, 32, 8, 128, 4, 131072, 64, 256, 4096, ZZ_ZIGZAG, {0, 1, 0, 1}, {});
